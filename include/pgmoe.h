@@ -1,0 +1,219 @@
+/*
+ * pgmoe.h - C ABI of libpgmoe: the per-layer sparse MoE block of Pre-gated MoE
+ * (arXiv 2308.12066) on one AMD MI355X (gfx950).
+ *
+ * What the library computes, per MoE block i of a stack of L blocks (Sec. II-B for the
+ * block, Sec. IV-B for the pre-gate wiring, Sec. IV-C for the migration):
+ *   1. a gate scores all E experts for every token (softmax over x.W) and the k best are
+ *      activated.  The gate that sits in block i is a PRE-gate: its result routes block i+1.
+ *      Block 0 additionally carries a conventional gate for itself; the last block has none.
+ *   2. only the activated experts of block i+1 are copied from pinned host memory into HBM,
+ *      on a copy stream, while block i executes (preemptive expert migration).  At most two
+ *      blocks' activated experts are resident (the peak-memory rule of Sec. IV-C).
+ *   3. block i's activated experts, each a dense FFN ReLU(x.W1).W2, process the tokens
+ *      routed to them, and each token's output is the sum over its experts of
+ *      (gate probability) x (expert output).
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative pgmoe_status; pgmoe_last_error()
+ *     gives the text.  Arguments are validated before anything is launched.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers ordinary host addresses,
+ *     "pinned" host memory obtained from hipHostMalloc.  The caller owns every buffer it
+ *     passes and keeps it alive until the stream work that uses it has completed.  The
+ *     library owns only the context: the expert slot pool, events and a small pinned
+ *     staging area.  No call allocates memory after pgmoe_create().
+ *   - Streams are hipStream_t passed as void* (NULL = the default stream).  All device work
+ *     is asynchronous on the given stream, except that pgmoe_fetch_experts() waits until the
+ *     routing indices have reached the host (it must read them to issue the copies).
+ *   - Matrices are row-major.  T = tokens in this call, d = d_model, f = d_ff, E = n_experts,
+ *     k = top_k.  Activations and gate weights have the context's dtype (float32 or
+ *     bfloat16); probabilities are float32; indices are int32.  T = 0 is a valid no-op.
+ *   - One context serves one stack on one device, from one host thread at a time.
+ */
+#ifndef PGMOE_H
+#define PGMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pgmoe_ctx pgmoe_ctx;
+
+typedef enum {
+    PGMOE_OK = 0,
+    PGMOE_EINVAL = -1,     /* null/misaligned pointer, size out of range, k > E, bad block ... */
+    PGMOE_ENOTPINNED = -2, /* host expert store is not pinned host memory */
+    PGMOE_ENOSLOT = -3,    /* more distinct experts selected than slots_per_gen */
+    PGMOE_EBADINDEX = -4,  /* an expert index outside [0, E) was seen on the host */
+    PGMOE_EHIP = -5,       /* a HIP runtime call failed (text has the HIP error) */
+    PGMOE_ENODEVICE = -6,  /* context was created host-only, or no GPU is present */
+    PGMOE_ESTATE = -7      /* call order violated (e.g. FFN of a block that was never fetched) */
+} pgmoe_status;
+
+typedef enum { PGMOE_F32 = 0, PGMOE_BF16 = 1 } pgmoe_dtype;
+
+/* Bits of pgmoe_config.flags */
+#define PGMOE_FLAG_HOST_ONLY 1u /* create no device resources: argument checks and host logic
+                                   work, every launch returns PGMOE_ENODEVICE */
+
+#define PGMOE_MAX_EXPERTS 256 /* the paper's largest model has 256 experts per block */
+
+typedef struct {
+    int32_t d_model;       /* bf16: multiple of 64; f32: any >= 1 */
+    int32_t d_ff;          /* bf16: multiple of 64 */
+    int32_t n_experts;     /* 1 .. PGMOE_MAX_EXPERTS */
+    int32_t top_k;         /* 1 .. n_experts */
+    int32_t n_blocks;      /* L >= 1 */
+    int32_t max_tokens;    /* largest T of any call */
+    int32_t dtype;         /* pgmoe_dtype of activations, gate weights and expert weights */
+    int32_t slots_per_gen; /* expert slots per block generation; 0 => min(E, max_tokens*k),
+                              which can never overflow.  Ignored without a host store. */
+    uint32_t flags;
+} pgmoe_config;
+
+/* Counters of the last pgmoe_fetch_experts() for a block (host). */
+typedef struct {
+    int32_t n_unique;       /* distinct experts selected */
+    int32_t n_copied;       /* experts actually copied (== n_unique in the base design) */
+    int64_t bytes_copied;   /* n_copied * expert_bytes */
+    int32_t resident_slots; /* slots holding live experts over both generations right after
+                               this fetch was issued: the quantity the peak-memory rule bounds */
+    int32_t reserved;
+    float fetch_ms;         /* copy-stream time of the batch (valid once it has completed) */
+    float wait_ms;          /* host time spent waiting for the indices */
+} pgmoe_fetch_stats;
+
+/* ---- context ---------------------------------------------------------------------- */
+int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg);
+int pgmoe_destroy(pgmoe_ctx *ctx);
+/* Text of the last error on this context (ctx == NULL: last error of a failed create or of
+ * a context-free call on this thread).  Never NULL; owned by the library. */
+const char *pgmoe_last_error(const pgmoe_ctx *ctx);
+
+/* Bytes of one expert blob (W1 then W2, contiguous): 2*d*f*sizeof(element). 0 if cfg invalid. */
+size_t pgmoe_expert_bytes(const pgmoe_config *cfg);
+/* Bytes of device scratch that pgmoe_expert_ffn() needs for up to max_tokens*k rows. */
+size_t pgmoe_workspace_bytes(const pgmoe_ctx *ctx);
+
+/* ---- expert weight layout (host) --------------------------------------------------
+ * An expert is handed to the library as one blob of pgmoe_expert_bytes().
+ *   f32 : W1 [d,f] row-major followed by W2 [f,d] row-major.
+ *   bf16: both matrices are stored as 32x16 (k x n) tiles of 512 elements so that one
+ *         64-lane load instruction fetches one matrix-core operand: element (k, n) of a
+ *         [K, N] matrix sits in tile (kt = k/32, nt = n/16) at in-tile position
+ *         ((n%16) + 16*((k%32)/8))*8 + k%8.  W1 (K=d, N=f) orders its tiles nt-major
+ *         (tile index nt*(K/32) + kt), W2 (K=f, N=d) kt-major (tile index kt*(N/16) + nt).
+ * pack/unpack convert between the logical row-major matrices and the blob; they are pure
+ * permutations (bit-exact, unpack(pack(W)) == W).  All pointers host. */
+int pgmoe_pack_expert(const pgmoe_config *cfg, const void *w1, const void *w2, void *blob);
+int pgmoe_unpack_expert(const pgmoe_config *cfg, const void *blob, void *w1, void *w2);
+
+/* ---- a-1: gate / pre-gate (Sec. II-B gate; Sec. IV-B pre-gate) ----------------------
+ * z = x.w_gate (+ bias); p = softmax over the E experts; the k largest z are selected, in
+ * descending order, equal values to the lowest index; a NaN logit ranks as -infinity.
+ *   x         dev [T,d]   ctx dtype      w_gate dev [d,E] ctx dtype     bias dev [E] f32 | NULL
+ *   topk_idx  dev [T,k]   int32 out      topk_prob dev [T,k] f32 out: p at the selected
+ *             experts, NOT renormalised  probs_out dev [T,E] f32 out | NULL (full softmax)
+ * Arithmetic: float32 accumulation and softmax.  The same call serves block 0's
+ * conventional gate and every pre-gate; which block its result routes is the caller's
+ * wiring (pgmoe_stack_step implements the paper's). */
+int pgmoe_pregate_topk(pgmoe_ctx *ctx, const void *x, const void *w_gate, const float *bias, int T,
+                       int32_t *topk_idx, float *topk_prob, float *probs_out, void *stream);
+
+/* ---- a-2: expert store and migration (Sec. IV-C) ------------------------------------
+ * Host store: blob of (block b, expert e) at host_base + b*block_stride + e*expert_stride,
+ * pinned.  Resident store: the same addressing in device memory (the GPU-only design point:
+ * nothing is migrated).  Exactly one of the two is active; registering one replaces the
+ * other.  Strides are multiples of 256 bytes and >= pgmoe_expert_bytes(). */
+int pgmoe_register_host_experts(pgmoe_ctx *ctx, const void *host_base, size_t expert_stride,
+                                size_t block_stride);
+int pgmoe_register_resident_experts(pgmoe_ctx *ctx, const void *dev_base, size_t expert_stride,
+                                    size_t block_stride);
+/* Copy the experts that `topk_idx` (dev [T,k], produced on compute_stream) selects for
+ * `block` into that block's slot generation (block & 1), on copy_stream.  The j-th smallest
+ * selected expert id goes to slot j.  Order of events: the indices are read back once
+ * compute_stream has produced them (the host waits for that); the copies wait until the
+ * FFN that last used this generation (block-2, or the previous step's) has finished; a
+ * done-event is recorded that pgmoe_expert_ffn(block) waits on.  With a resident store the
+ * call only validates and returns n_unique = -1 without touching the indices.
+ * n_unique_out host | NULL. */
+int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int T,
+                        void *compute_stream, void *copy_stream, int *n_unique_out);
+int pgmoe_get_fetch_stats(pgmoe_ctx *ctx, int block, pgmoe_fetch_stats *out /* host */);
+
+/* Host-only helper used by the fetch engine, exported for testing: ascending list of the
+ * distinct values of idx[0..n) (all must lie in [0, E)); returns their number or a negative
+ * status.  unique_out host [min(E, n)]. */
+int pgmoe_unique_experts(const int32_t *idx /* host */, int n, int E, int32_t *unique_out);
+
+/* ---- a-3: group tokens by expert (Sec. II-B: an expert processes the tokens routed to it)
+ * Entry n = t*k + j is token t's j-th selection.  counts[e] = entries routed to e;
+ * expert_offsets = exclusive prefix sum (E+1 values, last = T*k); row_of[n] = offsets[e] +
+ * number of earlier entries with the same expert (stable); x_perm[row_of[n]] = x[t].
+ *   x dev [T,d]; topk_idx dev [T,k]; x_perm dev [T*k,d] out; row_of dev [T*k] int32 out;
+ *   expert_offsets dev [E+1] int32 out.  An index outside [0,E) is clamped into range for
+ *   addressing and flagged: pgmoe_device_flags() reports it. */
+int pgmoe_permute(pgmoe_ctx *ctx, const void *x, const int32_t *topk_idx, int T, void *x_perm,
+                  int32_t *row_of, int32_t *expert_offsets, void *stream);
+
+/* ---- a-4: expert FFN -----------------------------------------------------------------
+ * For every expert e with rows [expert_offsets[e], expert_offsets[e+1]) of x_perm:
+ * y_perm[rows] = ReLU(x_perm[rows].W1_e).W2_e, weights taken from `block`'s slot generation
+ * (slot = rank of e among the experts with at least one row) or from the resident store.
+ * bf16: products on the matrix cores with float32 accumulation, the hidden activation
+ * rounded to bf16 between the two products; f32: float32 throughout.
+ *   x_perm dev [n_rows,d]; expert_offsets dev [E+1]; y_perm dev [n_rows,d] out;
+ *   workspace dev, pgmoe_workspace_bytes(), 256-byte aligned; n_rows = T*k <= max_tokens*k.
+ * With a host store the call first makes `stream` wait for the fetch of `block`
+ * (PGMOE_ESTATE if none was issued) and afterwards records the event that guards the slots'
+ * reuse. */
+int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_t *expert_offsets,
+                     int n_rows, void *y_perm, void *workspace, void *stream);
+
+/* ---- a-5: weighted combine -------------------------------------------------------------
+ * y[t] = sum_{j<k} topk_prob[t,j] * y_perm[row_of[t*k+j]]  (gather form, no atomics, float32
+ * accumulation, stored in ctx dtype).  If x_res and x_next are given, additionally
+ * x_next[t] = x_res[t] + (that sum), rounded once: the residual stand-in for the non-MoE
+ * layers between two MoE blocks.  y may be NULL when x_next is given.
+ *   y_perm dev [T*k,d]; row_of dev [T*k]; topk_prob dev [T,k]; y dev [T,d] out | NULL;
+ *   x_res dev [T,d] | NULL; x_next dev [T,d] out | NULL. */
+int pgmoe_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, const float *topk_prob,
+                  int T, void *y, const void *x_res, void *x_next, void *stream);
+
+/* ---- a-6: one pass of the whole stack (Sec. IV-B wiring + Sec. IV-C overlap) ------------
+ * Runs blocks 0..L-1 for one batch of T tokens:
+ *   block 0   : conventional gate on x_0 -> fetch(0) (exposed) ; pre-gate 0 on x_0 -> fetch(1)
+ *   block i   : [pre-gate i on x_i -> fetch(i+1) on the copy stream]  ||  permute, FFN_i,
+ *               combine on the compute stream, x_{i+1} = x_i + y_i
+ *   block L-1 : no gate.
+ * gate_w[0] / gate_b[0] is block 0's conventional gate, gate_w[g] / gate_b[g] for g >= 1 the
+ * pre-gate that sits in block g-1 (routes block g).  Arrays of pointers are host arrays of
+ * device pointers; gate_b or any gate_b[g] may be NULL. */
+typedef struct {
+    const void *const *gate_w;  /* host [L] -> dev [d,E] */
+    const float *const *gate_b; /* host [L] -> dev [E] | NULL; may itself be NULL */
+    void *x_states;             /* dev [(L+1), T, d]: in: x_states[0] = x_0; out: x_1..x_L */
+    void *y_blocks;             /* dev [L, T, d] out: y_i of every block | NULL */
+    int32_t *topk_idx;          /* dev [L, T, k] out: routing used by block i */
+    float *topk_prob;           /* dev [L, T, k] out */
+    int32_t *row_of;            /* dev [L, T*k] out */
+    int32_t *expert_offsets;    /* dev [L, E+1] out */
+    void *x_perm;               /* dev [T*k, d] scratch */
+    void *y_perm;               /* dev [T*k, d] scratch */
+    void *workspace;            /* dev, pgmoe_workspace_bytes() */
+} pgmoe_step_buffers;
+int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *compute_stream,
+                     void *copy_stream);
+
+/* Sticky device-side condition bits since the last call of this function (synchronises the
+ * device): bit 0 = a NaN logit was seen by a gate, bit 1 = an expert index outside [0,E)
+ * reached pgmoe_permute. */
+int pgmoe_device_flags(pgmoe_ctx *ctx, uint32_t *flags_out /* host */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PGMOE_H */

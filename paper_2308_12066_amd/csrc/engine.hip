@@ -1,0 +1,238 @@
+// Expert store, preemptive expert migration and the whole-stack step.
+//
+// Sec. IV-C of the paper: all experts live in host memory; once the pre-gate of block N has
+// picked block N+1's experts, only those are copied to the GPU while block N executes, and
+// the GPU holds the activated experts of two consecutive blocks at most.  Here that is a
+// slot pool of two generations (generation = block & 1).  Read-after-write: the FFN of a
+// block waits on the generation's fetch_done event.  Write-after-read: a fetch into a
+// generation waits on the ffn_done event of the block that used it last.
+#include <chrono>
+
+#include "pgmoe_internal.h"
+
+using namespace pgmoe;
+
+namespace {
+
+int check_store_args(pgmoe_ctx *ctx, const char *fn, const void *base, size_t expert_stride, size_t block_stride) {
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
+    if (!base) return fail(ctx, PGMOE_EINVAL, "%s: base is NULL", fn);
+    if (!aligned(base, 256)) return fail(ctx, PGMOE_EINVAL, "%s: base is not 256-byte aligned", fn);
+    if (expert_stride < ctx->expert_bytes || expert_stride % 256)
+        return fail(ctx, PGMOE_EINVAL, "%s: expert_stride=%zu must be a multiple of 256 and >= %zu", fn, expert_stride, ctx->expert_bytes);
+    if (block_stride < expert_stride * (size_t)ctx->cfg.n_experts || block_stride % 256)
+        return fail(ctx, PGMOE_EINVAL, "%s: block_stride=%zu must be a multiple of 256 and >= n_experts*expert_stride", fn, block_stride);
+    return PGMOE_OK;
+}
+
+int check_block(pgmoe_ctx *ctx, const char *fn, int block) {
+    if (block < 0 || block >= ctx->cfg.n_blocks) return fail(ctx, PGMOE_EINVAL, "%s: block=%d outside 0..%d", fn, block, ctx->cfg.n_blocks - 1);
+    return PGMOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pgmoe_register_host_experts(pgmoe_ctx *ctx, const void *host_base, size_t expert_stride, size_t block_stride) {
+    const char *fn = "pgmoe_register_host_experts";
+    int rc = check_store_args(ctx, fn, host_base, expert_stride, block_stride);
+    if (rc) return rc;
+    if (!ctx->host_only) {
+        hipPointerAttribute_t attr;
+        hipError_t e = hipPointerGetAttributes(&attr, host_base);
+        if (e != hipSuccess || attr.type != hipMemoryTypeHost) {
+            (void)hipGetLastError();
+            return fail(ctx, PGMOE_ENOTPINNED, "%s: host_base is not pinned host memory (allocate it with hipHostMalloc)", fn);
+        }
+        if (!ctx->slot_pool) {
+            const size_t bytes = (size_t)kGen * ctx->slots * ctx->expert_bytes;
+            PG_HIP(ctx, hipMalloc((void **)&ctx->slot_pool, bytes));
+        }
+    }
+    ctx->store_mode = STORE_HOST;
+    ctx->store_base = (const char *)host_base;
+    ctx->expert_stride = expert_stride;
+    ctx->block_stride = block_stride;
+    for (int g = 0; g < kGen; ++g) {
+        ctx->fetched_block[g] = -1;
+        ctx->live_slots[g] = 0;
+    }
+    return PGMOE_OK;
+}
+
+int pgmoe_register_resident_experts(pgmoe_ctx *ctx, const void *dev_base, size_t expert_stride, size_t block_stride) {
+    const char *fn = "pgmoe_register_resident_experts";
+    int rc = check_store_args(ctx, fn, dev_base, expert_stride, block_stride);
+    if (rc) return rc;
+    ctx->store_mode = STORE_RESIDENT;
+    ctx->store_base = (const char *)dev_base;
+    ctx->expert_stride = expert_stride;
+    ctx->block_stride = block_stride;
+    return PGMOE_OK;
+}
+
+int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int T, void *compute_stream,
+                        void *copy_stream, int *n_unique_out) {
+    const char *fn = "pgmoe_fetch_experts";
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
+    int rc = check_block(ctx, fn, block);
+    if (rc) return rc;
+    if (T < 0 || T > ctx->cfg.max_tokens) return fail(ctx, PGMOE_EINVAL, "%s: T=%d outside 0..max_tokens=%d", fn, T, ctx->cfg.max_tokens);
+    if (!topk_idx) return fail(ctx, PGMOE_EINVAL, "%s: topk_idx is NULL", fn);
+    if (!aligned(topk_idx, 4)) return fail(ctx, PGMOE_EINVAL, "%s: topk_idx is not 4-byte aligned", fn);
+    if (ctx->store_mode == STORE_NONE) return fail(ctx, PGMOE_ESTATE, "%s: no expert store registered", fn);
+    if (ctx->store_mode == STORE_RESIDENT) {
+        if (n_unique_out) *n_unique_out = -1;
+        return PGMOE_OK;
+    }
+    if (ctx->host_only) return fail(ctx, PGMOE_ENODEVICE, "%s: context is host-only, nothing can be launched", fn);
+    if (copy_stream == compute_stream) return fail(ctx, PGMOE_EINVAL, "%s: copy_stream must differ from compute_stream", fn);
+
+    hipStream_t cs = (hipStream_t)compute_stream, ps = (hipStream_t)copy_stream;
+    const int n = T * ctx->cfg.top_k;
+    const int gen = block & 1;
+    BlockStats &st = ctx->stats[block];
+    st = BlockStats();
+
+    // 1. bring the indices to the host (the only host wait of the block)
+    const auto t0 = std::chrono::steady_clock::now();
+    if (n > 0) {
+        PG_HIP(ctx, hipMemcpyAsync(ctx->idx_staging, topk_idx, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, cs));
+        PG_HIP(ctx, hipEventRecord(ctx->idx_ready, cs));
+        hipError_t q;
+        while ((q = hipEventQuery(ctx->idx_ready)) == hipErrorNotReady) {
+        }
+        if (q != hipSuccess) return hip_fail(ctx, q, "hipEventQuery(idx_ready)");
+    }
+    st.s.wait_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
+
+    // 2. distinct experts, ascending; slot j <- j-th of them
+    int32_t uniq[PGMOE_MAX_EXPERTS];
+    const int nu = pgmoe_unique_experts(ctx->idx_staging, n, ctx->cfg.n_experts, uniq);
+    if (nu < 0) return fail(ctx, nu, "%s: %s", fn, pgmoe_last_error(nullptr));
+    if (nu > ctx->slots) return fail(ctx, PGMOE_ENOSLOT, "%s: %d distinct experts selected but only %d slots per generation", fn, nu, ctx->slots);
+
+    // 3. the generation may still be read by the FFN that used it last
+    if (ctx->ffn_recorded[gen]) PG_HIP(ctx, hipStreamWaitEvent(ps, ctx->ffn_done[gen], 0));
+    PG_HIP(ctx, hipEventRecord(ctx->fetch_begin[block], ps));
+    char *gen_base = ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes;
+    const char *src_block = ctx->store_base + (size_t)block * ctx->block_stride;
+    for (int j = 0; j < nu; ++j)
+        PG_HIP(ctx, hipMemcpyAsync(gen_base + (size_t)j * ctx->expert_bytes, src_block + (size_t)uniq[j] * ctx->expert_stride,
+                                   ctx->expert_bytes, hipMemcpyHostToDevice, ps));
+    PG_HIP(ctx, hipEventRecord(ctx->fetch_end[block], ps));
+    PG_HIP(ctx, hipEventRecord(ctx->fetch_done[gen], ps));
+
+    ctx->fetched_block[gen] = block;
+    ctx->live_slots[gen] = nu;
+    st.timed = true;
+    st.s.n_unique = nu;
+    st.s.n_copied = nu;
+    st.s.bytes_copied = (int64_t)nu * (int64_t)ctx->expert_bytes;
+    // the other generation is live only if it holds a neighbouring block of this pass
+    const int other = ctx->fetched_block[gen ^ 1];
+    st.s.resident_slots = nu + ((other == block - 1 || other == block + 1) ? ctx->live_slots[gen ^ 1] : 0);
+    if (n_unique_out) *n_unique_out = nu;
+    return PGMOE_OK;
+}
+
+int pgmoe_get_fetch_stats(pgmoe_ctx *ctx, int block, pgmoe_fetch_stats *out) {
+    const char *fn = "pgmoe_get_fetch_stats";
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
+    int rc = check_block(ctx, fn, block);
+    if (rc) return rc;
+    if (!out) return fail(ctx, PGMOE_EINVAL, "%s: out is NULL", fn);
+    BlockStats &st = ctx->stats[block];
+    if (st.timed && !ctx->host_only) {
+        PG_HIP(ctx, hipEventSynchronize(ctx->fetch_end[block]));
+        float ms = 0.f;
+        PG_HIP(ctx, hipEventElapsedTime(&ms, ctx->fetch_begin[block], ctx->fetch_end[block]));
+        st.s.fetch_ms = ms;
+    }
+    *out = st.s;
+    return PGMOE_OK;
+}
+
+int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_t *expert_offsets, int n_rows,
+                     void *y_perm, void *workspace, void *stream) {
+    const char *fn = "pgmoe_expert_ffn";
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
+    int rc = check_block(ctx, fn, block);
+    if (rc) return rc;
+    const int64_t max_rows = (int64_t)ctx->cfg.max_tokens * ctx->cfg.top_k;
+    if (n_rows < 0 || n_rows > max_rows) return fail(ctx, PGMOE_EINVAL, "%s: n_rows=%d outside 0..%lld", fn, n_rows, (long long)max_rows);
+    if (!x_perm || !expert_offsets || !y_perm || !workspace) return fail(ctx, PGMOE_EINVAL, "%s: NULL pointer", fn);
+    if (!aligned(x_perm, 16) || !aligned(y_perm, 16) || !aligned(expert_offsets, 4) || !aligned(workspace, 256))
+        return fail(ctx, PGMOE_EINVAL, "%s: misaligned pointer (x_perm/y_perm 16, expert_offsets 4, workspace 256 bytes)", fn);
+    if (ctx->store_mode == STORE_NONE) return fail(ctx, PGMOE_ESTATE, "%s: no expert store registered", fn);
+    if (ctx->host_only) return fail(ctx, PGMOE_ENODEVICE, "%s: context is host-only, nothing can be launched", fn);
+    hipStream_t s = (hipStream_t)stream;
+    if (ctx->store_mode == STORE_RESIDENT)
+        return launch_ffn(ctx, ctx->store_base + (size_t)block * ctx->block_stride, ctx->expert_stride, false, x_perm,
+                          expert_offsets, n_rows, y_perm, workspace, s);
+    const int gen = block & 1;
+    if (ctx->fetched_block[gen] != block)
+        return fail(ctx, PGMOE_ESTATE, "%s: block %d was not fetched (generation holds block %d)", fn, block, ctx->fetched_block[gen]);
+    PG_HIP(ctx, hipStreamWaitEvent(s, ctx->fetch_done[gen], 0));
+    rc = launch_ffn(ctx, ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes, ctx->expert_bytes, true, x_perm,
+                    expert_offsets, n_rows, y_perm, workspace, s);
+    if (rc) return rc;
+    PG_HIP(ctx, hipEventRecord(ctx->ffn_done[gen], s));
+    ctx->ffn_recorded[gen] = true;
+    return PGMOE_OK;
+}
+
+int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *compute_stream, void *copy_stream) {
+    const char *fn = "pgmoe_stack_step";
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
+    if (!io) return fail(ctx, PGMOE_EINVAL, "%s: io is NULL", fn);
+    if (T < 0 || T > ctx->cfg.max_tokens) return fail(ctx, PGMOE_EINVAL, "%s: T=%d outside 0..max_tokens=%d", fn, T, ctx->cfg.max_tokens);
+    if (!io->gate_w || !io->x_states || !io->topk_idx || !io->topk_prob || !io->row_of || !io->expert_offsets ||
+        !io->x_perm || !io->y_perm || !io->workspace)
+        return fail(ctx, PGMOE_EINVAL, "%s: a required buffer is NULL", fn);
+    const pgmoe_config &c = ctx->cfg;
+    const int L = c.n_blocks;
+    for (int g = 0; g < L; ++g)
+        if (!io->gate_w[g]) return fail(ctx, PGMOE_EINVAL, "%s: gate_w[%d] is NULL", fn, g);
+    if (ctx->store_mode == STORE_NONE) return fail(ctx, PGMOE_ESTATE, "%s: no expert store registered", fn);
+    if (ctx->host_only) return fail(ctx, PGMOE_ENODEVICE, "%s: context is host-only, nothing can be launched", fn);
+    if (T == 0) return PGMOE_OK;
+
+    const size_t xbytes = (size_t)T * c.d_model * ctx->elem;
+    const size_t nk = (size_t)T * c.top_k;
+    auto x_at = [&](int i) { return (char *)io->x_states + (size_t)i * xbytes; };
+    auto idx_at = [&](int i) { return io->topk_idx + (size_t)i * nk; };
+    auto prob_at = [&](int i) { return io->topk_prob + (size_t)i * nk; };
+    auto bias_at = [&](int g) -> const float * { return io->gate_b ? io->gate_b[g] : nullptr; };
+    int rc;
+
+    // block 0: its own (conventional) gate, then an exposed fetch
+    rc = pgmoe_pregate_topk(ctx, x_at(0), io->gate_w[0], bias_at(0), T, idx_at(0), prob_at(0), nullptr, compute_stream);
+    if (rc) return rc;
+    rc = pgmoe_fetch_experts(ctx, 0, idx_at(0), T, compute_stream, copy_stream, nullptr);
+    if (rc) return rc;
+
+    for (int i = 0; i < L; ++i) {
+        // pre-gate of block i routes block i+1; its experts start moving before block i executes
+        if (i + 1 < L) {
+            rc = pgmoe_pregate_topk(ctx, x_at(i), io->gate_w[i + 1], bias_at(i + 1), T, idx_at(i + 1), prob_at(i + 1), nullptr,
+                                    compute_stream);
+            if (rc) return rc;
+            rc = pgmoe_fetch_experts(ctx, i + 1, idx_at(i + 1), T, compute_stream, copy_stream, nullptr);
+            if (rc) return rc;
+        }
+        int32_t *row_of = io->row_of + (size_t)i * nk;
+        int32_t *offs = io->expert_offsets + (size_t)i * (c.n_experts + 1);
+        rc = pgmoe_permute(ctx, x_at(i), idx_at(i), T, io->x_perm, row_of, offs, compute_stream);
+        if (rc) return rc;
+        rc = pgmoe_expert_ffn(ctx, i, io->x_perm, offs, (int)nk, io->y_perm, io->workspace, compute_stream);
+        if (rc) return rc;
+        void *y = io->y_blocks ? (char *)io->y_blocks + (size_t)i * xbytes : nullptr;
+        rc = pgmoe_combine(ctx, io->y_perm, row_of, prob_at(i), T, y, x_at(i), x_at(i + 1), compute_stream);
+        if (rc) return rc;
+    }
+    return PGMOE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,372 @@
+// Expert execution (Sec. II-B: every activated expert, a dense FFN, processes the tokens
+// routed to it):  y_perm[rows of e] = ReLU(x_perm[rows of e] . W1_e) . W2_e.
+//
+// bf16 path - one fused kernel, weights streamed from HBM exactly once per 16*MT-row chunk:
+//   workgroup = (chunk of <= 16*MT rows of one expert) x (a range of d_ff columns)
+//   = (blockIdx.x, blockIdx.y).
+//   It keeps the chunk's activations in LDS, already in matrix-core operand order, and walks
+//   its d_ff range in sub-slabs of SUB = 16*NW columns:
+//     phase A  wave w computes the 16 hidden features of n-tile w over the full d_model
+//              reduction (W1 tiles are contiguous in memory along k), applies ReLU, rounds to
+//              bf16 and drops the result into LDS in operand order for phase B;
+//     phase B  every wave multiplies that sub-slab of hidden features into its own d_model/NW
+//              output columns (W2 tiles of one k-tile are contiguous along n) and keeps the
+//              running output in registers across all sub-slabs.
+//   The hidden activation never leaves the CU.  With P > 1 d_ff ranges per chunk the partial
+//   outputs go to a float32 scratch [P][rows][d] and ffn_reduce_kernel adds them in fixed
+//   order (no atomics: results are bit-reproducible); with P == 1 the kernel writes y_perm.
+//   The weights are the A operand (v_mfma_f32_16x16x32_bf16, 16 features x 32 k) and the
+//   tokens the B operand, so each lane ends up with 4 consecutive features of one token.
+//
+// f32 path - plain float32 kernels (correctness configuration; no matrix cores).
+#include <algorithm>
+
+#include "pgmoe_internal.h"
+
+namespace pgmoe {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// ------------------------------------------------------------------------------------------
+// Which (expert, row range, slot) does chunk number `chunk` cover?  Chunks are numbered expert
+// by expert, ceil(n_e / rows_per_chunk) per expert.  Every wavefront computes this on its own
+// from the E+1 offsets (E <= 256: four experts per lane), so no LDS or barrier is needed.
+struct ChunkInfo {
+    int expert, slot, row0, nrows;  // nrows == 0: chunk does not exist
+};
+
+__device__ inline int wave_incl_scan(int v, int lane) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(v, off);
+        if (lane >= off) v += o;
+    }
+    return v;
+}
+
+__device__ inline ChunkInfo find_chunk(const int32_t *__restrict__ offsets, int E, int rows_per_chunk, int chunk) {
+    const int lane = threadIdx.x & 63;
+    ChunkInfo ci = {0, 0, 0, 0};
+    int chunk_base = 0, slot_base = 0;
+    for (int q = 0; q * 64 < E; ++q) {
+        const int e = q * 64 + lane;
+        int lo = 0, n = 0;
+        if (e < E) {
+            lo = offsets[e];
+            n = offsets[e + 1] - lo;
+        }
+        const int c = (n + rows_per_chunk - 1) / rows_per_chunk;
+        const int nz = n > 0 ? 1 : 0;
+        const int c_incl = wave_incl_scan(c, lane), nz_incl = wave_incl_scan(nz, lane);
+        const int c_excl = chunk_base + c_incl - c;
+        const bool mine = chunk >= c_excl && chunk < c_excl + c;
+        const unsigned long long hit = __ballot(mine);
+        if (hit) {
+            const int src = __ffsll((long long)hit) - 1;
+            const int first = (chunk - __shfl(c_excl, src)) * rows_per_chunk;
+            ci.expert = q * 64 + src;
+            ci.slot = slot_base + __shfl(nz_incl, src) - 1;
+            ci.row0 = __shfl(lo, src) + first;
+            ci.nrows = min(rows_per_chunk, __shfl(n, src) - first);
+            return ci;
+        }
+        chunk_base += __shfl(c_incl, 63);
+        slot_base += __shfl(nz_incl, 63);
+    }
+    return ci;
+}
+
+// ------------------------------------------------------------------------------------------
+template <int MT, int NTB, int NW>
+__global__ __launch_bounds__(NW * 64) void ffn_fused_kernel(
+    const __bf16 *__restrict__ x_perm, const int32_t *__restrict__ offsets, int E, int d, int f, int f_range,
+    const char *__restrict__ w_base, size_t w_stride, int slot_by_rank, float *__restrict__ partial,
+    __bf16 *__restrict__ y_perm, int n_rows) {
+    constexpr int SUB = 16 * NW;   // d_ff columns per sub-slab
+    constexpr int KTB = SUB / 32;  // k-tiles of phase B per sub-slab
+    constexpr int PA_UNROLL = 8;   // W1 tiles in flight per wave in phase A
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int KT = d >> 5;   // k-tiles of phase A
+    const int NTD = d >> 4;  // n-tiles of the output
+
+    const ChunkInfo ci = find_chunk(offsets, E, 16 * MT, blockIdx.x);
+    if (ci.nrows == 0) return;  // uniform over the workgroup
+
+    bf16x8 *xs = reinterpret_cast<bf16x8 *>(smem);             // [MT][KT][64] operand cells
+    bf16x8 *hs = xs + (size_t)MT * KT * 64;                    // [2][MT][KTB][64]
+
+    // stage the chunk's rows, zero-filling rows beyond nrows
+    {
+        const int cells_per_row = d >> 3;
+        const uint4 *src = reinterpret_cast<const uint4 *>(x_perm + (size_t)ci.row0 * d);
+        uint4 *dst = reinterpret_cast<uint4 *>(xs);
+        for (int i = tid; i < 16 * MT * cells_per_row; i += NW * 64) {
+            const int m = i / cells_per_row, k8 = i - m * cells_per_row;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (m < ci.nrows) v = src[(size_t)m * cells_per_row + k8];
+            dst[(((m >> 4) * KT + (k8 >> 2)) << 6) + (m & 15) + 16 * (k8 & 3)] = v;
+        }
+    }
+    __syncthreads();
+
+    const char *wexp = w_base + (size_t)(slot_by_rank ? ci.slot : ci.expert) * w_stride;
+    const bf16x8 *w1 = reinterpret_cast<const bf16x8 *>(wexp);
+    const bf16x8 *w2 = reinterpret_cast<const bf16x8 *>(wexp + (size_t)d * f * 2);
+
+    floatx4 yacc[NTB][MT];
+#pragma unroll
+    for (int a = 0; a < NTB; ++a)
+#pragma unroll
+        for (int m = 0; m < MT; ++m) yacc[a][m] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const int f0 = blockIdx.y * f_range;
+    const int q = lane >> 4;
+    int buf = 0;
+    for (int fs = f0; fs < f0 + f_range; fs += SUB, buf ^= 1) {
+        // ---- phase A: hidden features [fs + 16*wave, +16) for all rows of the chunk
+        floatx4 hacc[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) hacc[m] = floatx4{0.f, 0.f, 0.f, 0.f};
+        const bf16x8 *wa = w1 + ((size_t)((fs >> 4) + wave) * KT << 6) + lane;
+        int kt = 0;
+        for (; kt + PA_UNROLL <= KT; kt += PA_UNROLL) {
+            bf16x8 a[PA_UNROLL];
+#pragma unroll
+            for (int u = 0; u < PA_UNROLL; ++u) a[u] = wa[(size_t)(kt + u) << 6];
+#pragma unroll
+            for (int u = 0; u < PA_UNROLL; ++u)
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    hacc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], xs[((m * KT + kt + u) << 6) + lane], hacc[m], 0, 0, 0);
+        }
+        for (; kt < KT; ++kt) {
+            const bf16x8 a = wa[(size_t)kt << 6];
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+                hacc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, xs[((m * KT + kt) << 6) + lane], hacc[m], 0, 0, 0);
+        }
+        // ReLU, round to bf16, store as phase-B operand: feature 16*wave + 4*q + r is k-tile
+        // wave/2, k-group 2*(wave%2) + q/2, position 4*(q%2) + r of the cell of token lane%16.
+        {
+            char *hbase = reinterpret_cast<char *>(hs + (size_t)buf * MT * KTB * 64);
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                bf16x4 h;
+                h.x = (__bf16)fmaxf(hacc[m].x, 0.f);
+                h.y = (__bf16)fmaxf(hacc[m].y, 0.f);
+                h.z = (__bf16)fmaxf(hacc[m].z, 0.f);
+                h.w = (__bf16)fmaxf(hacc[m].w, 0.f);
+                const int cell = ((m * KTB + (wave >> 1)) << 6) + (lane & 15) + 16 * (2 * (wave & 1) + (q >> 1));
+                *reinterpret_cast<bf16x4 *>(hbase + (size_t)cell * 16 + 8 * (q & 1)) = h;
+            }
+        }
+        __syncthreads();
+        // ---- phase B: y[:, wave's columns] += H_sub . W2[fs .. fs+SUB, wave's columns]
+        const bf16x8 *hb = hs + (size_t)buf * MT * KTB * 64;
+#pragma unroll
+        for (int kb = 0; kb < KTB; ++kb) {
+            const bf16x8 *wb = w2 + (((size_t)((fs >> 5) + kb) * NTD + wave * NTB) << 6) + lane;
+            bf16x8 hfrag[MT];
+#pragma unroll
+            for (int m = 0; m < MT; ++m) hfrag[m] = hb[((m * KTB + kb) << 6) + lane];
+#pragma unroll
+            for (int a = 0; a < NTB; ++a) {
+                const bf16x8 wv = wb[(size_t)a << 6];
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    yacc[a][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, hfrag[m], yacc[a][m], 0, 0, 0);
+            }
+        }
+        // no second barrier: the next sub-slab writes the other half of hs
+    }
+
+    // ---- epilogue: lane holds token (lane%16) of tile m, output columns 16*(wave*NTB+a) + 4*q + {0..3}
+    const int tok = lane & 15;
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const int r = m * 16 + tok;
+        if (r >= ci.nrows) continue;
+        const size_t row = (size_t)ci.row0 + r;
+        if (partial) {
+            float *dst = partial + ((size_t)blockIdx.y * n_rows + row) * d + (wave * NTB) * 16 + 4 * q;
+#pragma unroll
+            for (int a = 0; a < NTB; ++a) *reinterpret_cast<floatx4 *>(dst + a * 16) = yacc[a][m];
+        } else {
+            __bf16 *dst = y_perm + row * d + (wave * NTB) * 16 + 4 * q;
+#pragma unroll
+            for (int a = 0; a < NTB; ++a) {
+                bf16x4 o;
+                o.x = (__bf16)yacc[a][m].x;
+                o.y = (__bf16)yacc[a][m].y;
+                o.z = (__bf16)yacc[a][m].z;
+                o.w = (__bf16)yacc[a][m].w;
+                *reinterpret_cast<bf16x4 *>(dst + a * 16) = o;
+            }
+        }
+    }
+}
+
+// y_perm[row][c] = bf16( sum_p partial[p][row][c] ), p ascending.
+__global__ __launch_bounds__(256) void ffn_reduce_kernel(const float *__restrict__ partial, int P, int n_rows, int d,
+                                                          __bf16 *__restrict__ y_perm) {
+    const size_t total4 = (size_t)n_rows * d / 4;
+    const size_t stride4 = total4;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total4; i += (size_t)gridDim.x * 256) {
+        const floatx4 *src = reinterpret_cast<const floatx4 *>(partial) + i;
+        floatx4 s = src[0];
+        for (int p = 1; p < P; ++p) s += src[(size_t)p * stride4];
+        bf16x4 o;
+        o.x = (__bf16)s.x;
+        o.y = (__bf16)s.y;
+        o.z = (__bf16)s.z;
+        o.w = (__bf16)s.w;
+        reinterpret_cast<bf16x4 *>(y_perm)[i] = o;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// float32 path.  One workgroup per (row = blockIdx.x, 256 output columns = blockIdx.y); the row's expert and slot are
+// found once per workgroup.
+__device__ inline void find_row_expert(const int32_t *offsets, int E, int row, int *expert, int *slot) {
+    int e = 0, s = -1;
+    for (int i = 0; i < E; ++i) {
+        const int lo = offsets[i], hi = offsets[i + 1];
+        if (hi > lo) ++s;
+        if (row >= lo && row < hi) {
+            e = i;
+            break;
+        }
+    }
+    *expert = e;
+    *slot = s < 0 ? 0 : s;
+}
+
+__global__ __launch_bounds__(256) void ffn_f32_hidden_kernel(const float *__restrict__ x_perm,
+                                                              const int32_t *__restrict__ offsets, int E, int d, int f,
+                                                              const char *__restrict__ w_base, size_t w_stride,
+                                                              int slot_by_rank, float *__restrict__ h) {
+    __shared__ int s_e, s_s;
+    const int row = blockIdx.x;
+    if (threadIdx.x == 0) find_row_expert(offsets, E, row, &s_e, &s_s);
+    __syncthreads();
+    const float *w1 = reinterpret_cast<const float *>(w_base + (size_t)(slot_by_rank ? s_s : s_e) * w_stride);
+    const int j = blockIdx.y * 256 + threadIdx.x;
+    if (j >= f) return;
+    const float *xr = x_perm + (size_t)row * d;
+    float acc = 0.f;
+    for (int i = 0; i < d; ++i) acc = fmaf(xr[i], w1[(size_t)i * f + j], acc);
+    h[(size_t)row * f + j] = fmaxf(acc, 0.f);
+}
+
+__global__ __launch_bounds__(256) void ffn_f32_out_kernel(const float *__restrict__ h, const int32_t *__restrict__ offsets,
+                                                           int E, int d, int f, const char *__restrict__ w_base,
+                                                           size_t w_stride, int slot_by_rank, float *__restrict__ y_perm) {
+    __shared__ int s_e, s_s;
+    const int row = blockIdx.x;
+    if (threadIdx.x == 0) find_row_expert(offsets, E, row, &s_e, &s_s);
+    __syncthreads();
+    const float *w2 = reinterpret_cast<const float *>(w_base + (size_t)(slot_by_rank ? s_s : s_e) * w_stride) + (size_t)d * f;
+    const int c = blockIdx.y * 256 + threadIdx.x;
+    if (c >= d) return;
+    const float *hr = h + (size_t)row * f;
+    float acc = 0.f;
+    for (int j = 0; j < f; ++j) acc = fmaf(hr[j], w2[(size_t)j * d + c], acc);
+    y_perm[(size_t)row * d + c] = acc;
+}
+
+// ------------------------------------------------------------------------------------------
+static int smallest_divisor_at_least(int n, int want) {
+    for (int p = std::max(1, want); p <= n; ++p)
+        if (n % p == 0) return p;
+    return n;
+}
+
+FfnPlan plan_ffn(const pgmoe_config &c, int n_rows) {
+    FfnPlan p;
+    const int E = c.n_experts;
+    const int mean_rows = (n_rows + E - 1) / E;
+    const int ntb = c.d_model / 64;  // output n-tiles per wave with 4 waves
+    int mt = mean_rows <= 4 ? 1 : (mean_rows <= 20 ? 2 : 4);
+    while (mt > 1 && (ntb * mt > 48 || (size_t)mt * c.d_model * 32 + 4096u * mt > 150u * 1024u)) mt >>= 1;
+    p.mt = mt;
+    const int active = std::max(1, std::min(E, n_rows));
+    p.max_chunks = active + n_rows / (16 * mt);
+    const int nsub = c.d_ff / kSub;
+    const int want = (768 + active - 1) / active;  // aim at >= 768 workgroups
+    p.n_partial = smallest_divisor_at_least(nsub, std::min(want, nsub));
+    p.f_range = c.d_ff / p.n_partial;
+    return p;
+}
+
+size_t ffn_workspace_bytes(const pgmoe_config &c) {
+    const int64_t max_rows = (int64_t)c.max_tokens * c.top_k;
+    if (c.dtype == PGMOE_F32) return (size_t)max_rows * c.d_ff * 4;
+    size_t best = 256;
+    auto consider = [&](int n) {
+        const FfnPlan p = plan_ffn(c, n);
+        if (p.n_partial > 1) best = std::max(best, (size_t)p.n_partial * n * c.d_model * 4);
+    };
+    for (int n = 1; n <= std::min<int64_t>(max_rows, c.n_experts); ++n) consider(n);
+    consider((int)max_rows);
+    return (best + 255) & ~(size_t)255;
+}
+
+template <int MT, int NTB>
+static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, size_t w_stride, bool slot_by_rank,
+                        const void *x_perm, const int32_t *offsets, int n_rows, void *y_perm, void *workspace,
+                        hipStream_t s) {
+    constexpr int NW = 4;
+    const pgmoe_config &c = ctx->cfg;
+    const size_t lds = (size_t)MT * (c.d_model / 32) * 1024 + 2u * MT * (16 * NW / 32) * 1024;
+    auto kern = ffn_fused_kernel<MT, NTB, NW>;
+    static thread_local size_t lds_set = 0;  // per instantiation
+    if (lds > 48 * 1024 && lds > lds_set) {
+        PG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        lds_set = lds;
+    }
+    float *partial = p.n_partial > 1 ? (float *)workspace : nullptr;
+    hipLaunchKernelGGL(kern, dim3(p.max_chunks, p.n_partial), dim3(NW * 64), lds, s, (const __bf16 *)x_perm, offsets,
+                       c.n_experts, c.d_model, c.d_ff, p.f_range, w_base, w_stride, slot_by_rank ? 1 : 0, partial,
+                       (__bf16 *)y_perm, n_rows);
+    PG_HIP(ctx, hipGetLastError());
+    if (partial) {
+        const size_t total4 = (size_t)n_rows * c.d_model / 4;
+        const int grid = (int)std::min<size_t>((total4 + 255) / 256, 4096);
+        hipLaunchKernelGGL(ffn_reduce_kernel, dim3(grid), dim3(256), 0, s, partial, p.n_partial, n_rows, c.d_model,
+                           (__bf16 *)y_perm);
+        PG_HIP(ctx, hipGetLastError());
+    }
+    return PGMOE_OK;
+}
+
+int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, const void *x_perm,
+               const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s) {
+    const pgmoe_config &c = ctx->cfg;
+    if (n_rows == 0) return PGMOE_OK;
+    if (c.dtype == PGMOE_F32) {
+        float *h = (float *)workspace;
+        hipLaunchKernelGGL(ffn_f32_hidden_kernel, dim3(n_rows, (c.d_ff + 255) / 256), dim3(256), 0, s,
+                           (const float *)x_perm, offsets, c.n_experts, c.d_model, c.d_ff, w_base, w_stride,
+                           slot_by_rank ? 1 : 0, h);
+        PG_HIP(ctx, hipGetLastError());
+        hipLaunchKernelGGL(ffn_f32_out_kernel, dim3(n_rows, (c.d_model + 255) / 256), dim3(256), 0, s, h, offsets,
+                           c.n_experts, c.d_model, c.d_ff, w_base, w_stride, slot_by_rank ? 1 : 0, (float *)y_perm);
+        PG_HIP(ctx, hipGetLastError());
+        return PGMOE_OK;
+    }
+    const FfnPlan p = plan_ffn(c, n_rows);
+    const int ntb = c.d_model / 64;
+#define PG_CASE(MT_, NTB_) \
+    if (p.mt == MT_ && ntb == NTB_) return launch_fused<MT_, NTB_>(ctx, p, w_base, w_stride, slot_by_rank, x_perm, offsets, n_rows, y_perm, workspace, s)
+    PG_CASE(1, 1); PG_CASE(1, 2); PG_CASE(1, 4); PG_CASE(1, 8); PG_CASE(1, 12); PG_CASE(1, 16); PG_CASE(1, 32);
+    PG_CASE(2, 1); PG_CASE(2, 2); PG_CASE(2, 4); PG_CASE(2, 8); PG_CASE(2, 12); PG_CASE(2, 16);
+    PG_CASE(4, 1); PG_CASE(4, 2); PG_CASE(4, 4); PG_CASE(4, 8); PG_CASE(4, 12);
+#undef PG_CASE
+    return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: no bf16 kernel built for d_model=%d (supported: 64, 128, 256, 512, 768, 1024, 2048)", c.d_model);
+}
+
+}  // namespace pgmoe

@@ -1,0 +1,101 @@
+// Internal declarations shared by the translation units of libpgmoe (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+
+#include "pgmoe.h"
+
+namespace pgmoe {
+
+enum StoreMode { STORE_NONE = 0, STORE_HOST = 1, STORE_RESIDENT = 2 };
+
+constexpr int kGen = 2;  // block generations resident at once (current + next block)
+
+// Device-side sticky condition bits (see pgmoe_device_flags).
+constexpr uint32_t kFlagNaN = 1u;
+constexpr uint32_t kFlagBadIndex = 2u;
+
+// Rows of one expert that a single FFN workgroup handles at once (bf16 path): 16 * MT.
+constexpr int kTileRows = 16;
+// Width of the d_ff sub-slab a workgroup pushes through both products before moving on.
+constexpr int kSub = 64;
+
+struct BlockStats {
+    pgmoe_fetch_stats s;
+    bool timed;  // fetch_begin/fetch_end were recorded for this block
+};
+
+}  // namespace pgmoe
+
+struct pgmoe_ctx {
+    pgmoe_config cfg;
+    bool host_only;
+    int device;
+    size_t elem;          // bytes per activation / weight element
+    size_t expert_bytes;  // 2*d*f*elem
+    int slots;            // slots per generation
+
+    // expert store
+    int store_mode;
+    const char *store_base;
+    size_t expert_stride, block_stride;
+
+    // device resources
+    char *slot_pool;       // [kGen][slots][expert_bytes]
+    uint32_t *dev_flags;   // sticky condition bits
+    int32_t *idx_staging;  // pinned host [max_tokens * k]
+    hipEvent_t idx_ready;
+    hipEvent_t fetch_done[pgmoe::kGen];
+    hipEvent_t ffn_done[pgmoe::kGen];
+    hipEvent_t *fetch_begin;  // [n_blocks] timing
+    hipEvent_t *fetch_end;    // [n_blocks]
+    int fetched_block[pgmoe::kGen];  // block whose experts the generation holds (-1: none)
+    int live_slots[pgmoe::kGen];
+    bool ffn_recorded[pgmoe::kGen];
+    pgmoe::BlockStats *stats;  // [n_blocks]
+
+    char err[512];
+};
+
+namespace pgmoe {
+
+int fail(pgmoe_ctx *ctx, int code, const char *fmt, ...) __attribute__((format(printf, 3, 4)));
+int hip_fail(pgmoe_ctx *ctx, hipError_t e, const char *what);
+// Validates cfg; on failure writes the reason to buf and returns PGMOE_EINVAL.
+int check_config(const pgmoe_config *cfg, char *buf, size_t n);
+
+#define PG_HIP(ctx, call)                                               \
+    do {                                                                \
+        hipError_t e_ = (call);                                         \
+        if (e_ != hipSuccess) return ::pgmoe::hip_fail(ctx, e_, #call); \
+    } while (0)
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Geometry of the bf16 FFN launch for n_rows permuted rows (host side, deterministic):
+// rows per workgroup chunk, number of d_ff ranges (partial sums) and the chunk-count bound.
+struct FfnPlan {
+    int mt;          // 16-row tiles per chunk (1, 2 or 4)
+    int f_range;     // d_ff columns per workgroup (multiple of kSub)
+    int n_partial;   // d_ff / f_range
+    int max_chunks;  // upper bound of sum_e ceil(n_e / (16*mt))
+};
+FfnPlan plan_ffn(const pgmoe_config &cfg, int n_rows);
+size_t ffn_workspace_bytes(const pgmoe_config &cfg);
+
+// Kernel launchers (each validates nothing: callers did).  All asynchronous on `s`.
+int launch_gate(pgmoe_ctx *ctx, const void *x, const void *w, const float *bias, int T, int32_t *idx,
+                float *prob, float *probs, hipStream_t s);
+int launch_permute(pgmoe_ctx *ctx, const void *x, const int32_t *idx, int T, void *x_perm,
+                   int32_t *row_of, int32_t *offsets, hipStream_t s);
+int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, const void *x_perm,
+               const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s);
+int launch_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, const float *prob, int T,
+                   void *y, const void *x_res, void *x_next, hipStream_t s);
+
+}  // namespace pgmoe

@@ -1,0 +1,154 @@
+"""Host-side checks of libpgmoe that need no GPU: the library loads and exports every symbol
+the header declares, arguments are validated before anything is launched, and the host
+helpers (weight tiling, unique-expert list) are exact."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2308_12066_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "pgmoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pgmoe_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = header_functions()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(B.lib, n), f"{n} declared in pgmoe.h but not exported"
+    assert sorted(B.EXPORTS) == names
+
+
+def cfg(**kw):
+    base = dict(d_model=64, d_ff=128, n_experts=8, top_k=2, n_blocks=3, max_tokens=32, dtype=B.BF16,
+                slots_per_gen=0, flags=B.FLAG_HOST_ONLY)
+    base.update(kw)
+    return B.make_config(**base)
+
+
+@pytest.mark.parametrize("bad", [dict(dtype=7), dict(d_model=0), dict(d_model=96), dict(d_ff=100), dict(n_experts=0),
+                                 dict(n_experts=257), dict(top_k=0), dict(top_k=9), dict(n_blocks=0),
+                                 dict(max_tokens=0), dict(slots_per_gen=9), dict(flags=64), dict(d_model=4096)])
+def test_create_rejects_bad_config(bad):
+    with pytest.raises(B.PgmoeError) as ei:
+        B.Context(cfg(**bad))
+    assert ei.value.code == B.EINVAL and "pgmoe_create" in str(ei.value)
+    assert B.expert_bytes(cfg(**bad)) == 0
+
+
+def test_expert_bytes():
+    assert B.expert_bytes(cfg(d_model=768, d_ff=3072)) == 9437184
+    assert B.expert_bytes(cfg(d_model=1024, d_ff=4096)) == 16777216
+    assert B.expert_bytes(cfg(d_model=64, d_ff=256, dtype=B.F32)) == 131072
+
+
+def test_host_only_context_validates_then_refuses_to_launch():
+    c = B.Context(cfg())
+    buf = np.zeros(1 << 16, dtype=np.uint8)      # 16-byte aligned host memory standing in for pointers
+    p = buf.ctypes.data + (-buf.ctypes.data) % 256
+    with pytest.raises(B.PgmoeError) as ei:
+        c.pregate_topk(p, p, None, 4, p, p)
+    assert ei.value.code == B.ENODEVICE
+    with pytest.raises(B.PgmoeError) as ei:
+        c.pregate_topk(p, p, None, 33, p, p)      # T > max_tokens
+    assert ei.value.code == B.EINVAL and "max_tokens" in str(ei.value)
+    with pytest.raises(B.PgmoeError) as ei:
+        c.pregate_topk(None, p, None, 4, p, p)
+    assert ei.value.code == B.EINVAL and "NULL" in str(ei.value)
+    with pytest.raises(B.PgmoeError) as ei:
+        c.pregate_topk(p + 2, p, None, 4, p, p)
+    assert ei.value.code == B.EINVAL and "aligned" in str(ei.value)
+    with pytest.raises(B.PgmoeError) as ei:
+        c.permute(p, p, -1, p, p, p)
+    assert ei.value.code == B.EINVAL
+    with pytest.raises(B.PgmoeError) as ei:
+        c.combine(p, p, p, 4, None, None, None)
+    assert ei.value.code == B.EINVAL and "both" in str(ei.value)
+    with pytest.raises(B.PgmoeError) as ei:
+        c.combine(p, p, p, 4, p, p, None)
+    assert ei.value.code == B.EINVAL
+    with pytest.raises(B.PgmoeError) as ei:
+        c.expert_ffn(0, p, p, 8, p, p)
+    assert ei.value.code == B.ESTATE                # no store registered
+    with pytest.raises(B.PgmoeError) as ei:
+        c.expert_ffn(3, p, p, 8, p, p)
+    assert ei.value.code == B.EINVAL and "block" in str(ei.value)
+    with pytest.raises(B.PgmoeError) as ei:
+        c.fetch_experts(0, p, 4, None, None)
+    assert ei.value.code == B.ESTATE
+    eb = B.expert_bytes(c.cfg)
+    with pytest.raises(B.PgmoeError) as ei:
+        c.register_host_experts(p, eb - 256, 8 * eb)
+    assert ei.value.code == B.EINVAL
+    with pytest.raises(B.PgmoeError) as ei:
+        c.register_host_experts(p, eb, 7 * eb)
+    assert ei.value.code == B.EINVAL
+    c.register_resident_experts(p, eb, 8 * eb)
+    assert c.fetch_experts(1, p, 4, None, None) == -1      # resident store: nothing to migrate
+    with pytest.raises(B.PgmoeError) as ei:
+        c.expert_ffn(0, p, p, 65, p, p)             # n_rows > max_tokens*k
+    assert ei.value.code == B.EINVAL
+    with pytest.raises(B.PgmoeError) as ei:
+        c.expert_ffn(0, p, p, 8, p, p)
+    assert ei.value.code == B.ENODEVICE
+    assert c.workspace_bytes > 0
+    c.close()
+
+
+def tiled_position(k, n, K, N, nt_major):
+    """The layout rule of pgmoe.h retyped in numpy (vectorised over k, n)."""
+    kt, nt = k // 32, n // 16
+    tile = np.where(nt_major, nt * (K // 32) + kt, kt * (N // 16) + nt)
+    lane = (n % 16) + 16 * ((k % 32) // 8)
+    return tile * 512 + lane * 8 + (k % 8)
+
+
+@pytest.mark.parametrize("d,f", [(64, 128), (128, 64), (192, 320)])
+def test_pack_is_the_documented_permutation_and_unpack_inverts_it(d, f):
+    c = cfg(d_model=d, d_ff=f)
+    g = np.random.default_rng(d + f)
+    w1 = g.integers(0, 65536, size=(d, f)).astype(np.uint16)
+    w2 = g.integers(0, 65536, size=(f, d)).astype(np.uint16)
+    blob = np.zeros(2 * d * f, dtype=np.uint16)
+    B.pack_expert(c, w1, w2, blob)
+    k, n = np.meshgrid(np.arange(d), np.arange(f), indexing="ij")
+    exp1 = np.zeros(d * f, dtype=np.uint16)
+    exp1[tiled_position(k, n, d, f, True)] = w1
+    k, n = np.meshgrid(np.arange(f), np.arange(d), indexing="ij")
+    exp2 = np.zeros(d * f, dtype=np.uint16)
+    exp2[tiled_position(k, n, f, d, False)] = w2
+    assert np.array_equal(blob[: d * f], exp1) and np.array_equal(blob[d * f:], exp2)
+    u1, u2 = np.zeros_like(w1), np.zeros_like(w2)
+    B.unpack_expert(c, blob, u1, u2)
+    assert np.array_equal(u1, w1) and np.array_equal(u2, w2)
+
+
+def test_pack_f32_is_plain_concatenation():
+    c = cfg(d_model=6, d_ff=10, dtype=B.F32)
+    g = np.random.default_rng(0)
+    w1 = g.standard_normal((6, 10)).astype(np.float32)
+    w2 = g.standard_normal((10, 6)).astype(np.float32)
+    blob = np.zeros(120, dtype=np.float32)
+    B.pack_expert(c, w1, w2, blob)
+    assert np.array_equal(blob, np.concatenate([w1.ravel(), w2.ravel()]))
+
+
+def test_unique_experts():
+    g = np.random.default_rng(3)
+    for n, E in ((0, 4), (1, 1), (16, 64), (4096, 128), (200, 256)):
+        idx = g.integers(0, E, size=n).astype(np.int32)
+        assert np.array_equal(B.unique_experts(idx, E), np.unique(idx))
+    with pytest.raises(B.PgmoeError) as ei:
+        B.unique_experts(np.array([0, 5, 2], dtype=np.int32), 5)
+    assert ei.value.code == B.EBADINDEX
+    with pytest.raises(B.PgmoeError) as ei:
+        B.unique_experts(np.array([-1], dtype=np.int32), 5)
+    assert ei.value.code == B.EBADINDEX
