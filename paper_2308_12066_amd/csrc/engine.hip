@@ -130,9 +130,9 @@ int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int 
     st.s.n_unique = nu;
     st.s.n_copied = nu;
     st.s.bytes_copied = (int64_t)nu * (int64_t)ctx->expert_bytes;
-    // the other generation is live only if it holds a neighbouring block of this pass
-    const int other = ctx->fetched_block[gen ^ 1];
-    st.s.resident_slots = nu + ((other == block - 1 || other == block + 1) ? ctx->live_slots[gen ^ 1] : 0);
+    // the other generation is live only if it holds the block that executes while this fetch
+    // runs (block - 1); anything else in it is left over from an earlier pass
+    st.s.resident_slots = nu + (ctx->fetched_block[gen ^ 1] == block - 1 ? ctx->live_slots[gen ^ 1] : 0);
     if (n_unique_out) *n_unique_out = nu;
     return PGMOE_OK;
 }

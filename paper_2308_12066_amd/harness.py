@@ -46,7 +46,7 @@ class ExpertStore:
                  get_expert=None, pinned: bool = True):
         self.w, self.cfg = w, cfg
         self.expert_bytes = B.expert_bytes(cfg)
-        self.expert_stride = self.expert_bytes
+        self.expert_stride = (self.expert_bytes + 255) // 256 * 256
         self.block_stride = self.expert_stride * w.n_experts
         total = self.block_stride * w.n_blocks
         pin = pinned and torch.cuda.is_available()
