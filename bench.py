@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the pre-gated MoE hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+
+A "step" is one pass of the whole hot path over one batch: conventional gate of block 0,
+pre-gates, migration of the pre-gated experts from pinned host memory, token grouping,
+expert FFNs and weighted combine, for all L blocks of the stack.  Inputs (hidden states of
+every step, gate weights) are resident in HBM before the timed region; the expert store is in
+pinned host memory (offloaded workloads) or in HBM (resident workloads), as the workload says.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
+LINK_PEAK_GBPS = 64.0       # PCIe gen5 x16, per direction, nominal
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(w, steps_sample):
+    """Time the CPU oracle (as it stands) on a bounded sample of the same workload."""
+    import numpy as np
+
+    import workloads as W
+    from oracle import reference as R
+
+    gates = W.gate_tensors(w)
+    cache = {}
+
+    def get(b, e):
+        if (b, e) not in cache:
+            w1, w2 = W.expert_weights(w, b, e)
+            cache[(b, e)] = (W.to_bf16_bits(w1), W.to_bf16_bits(w2)) if w.dtype == "bf16" else (w1, w2)
+        return cache[(b, e)]
+
+    xs = [W.step_input(w, s) for s in range(steps_sample)]
+    for x in xs:                                    # untimed pass: generates the experts the routing needs
+        R.stack_forward(x, gates, w.top_k, get, w.d_ff)
+    t0 = time.perf_counter()
+    for x in xs:
+        R.stack_forward(x, gates, w.top_k, get, w.d_ff)
+    dt = time.perf_counter() - t0
+    threads = min(R.max_threads(), w.tokens)        # the oracle parallelises over tokens only
+    return {"value": w.tokens * steps_sample / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{steps_sample} steps x {w.n_blocks} blocks x {w.tokens} tokens of {w.name} (fp64, routed), "
+                      f"{dt:.2f} s; expert weight generation excluded",
+            "ms_per_token_per_layer": 1e3 * dt / (w.tokens * steps_sample * w.n_blocks)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-steps", type=int, default=None)
+    ap.add_argument("--host-threads", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import workloads as W
+    from paper_2308_12066_amd import harness as H
+
+    w = W.CONFIGS[args.workload]
+    K = args.steps if args.steps is not None else w.steps
+    Wm = args.warmup if args.warmup is not None else max(3, min(16, K // 8))
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    L, T, k, E = w.n_blocks, w.tokens, w.top_k, w.n_experts
+
+    t0 = time.perf_counter()
+    cfg = H.config_for(w)
+    store = H.ExpertStore(w, cfg, threads=args.host_threads)
+    stack = H.Stack(w, store)
+    n_in = min(K + Wm, max(w.steps, 8))              # distinct step inputs (cycled if K + W is larger)
+    x_in = torch.stack([H.to_device(W.step_input(w, s), w.dtype) for s in range(n_in)])
+    idx_log = torch.zeros((K, L, T, k), dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    log(f"[bench] {w.name}: store {store.host.numel() / 2**30:.2f} GiB built in {time.perf_counter() - t0:.1f} s")
+
+    def run(first, count, log_idx):
+        with torch.cuda.stream(stack.compute):
+            for s in range(first, first + count):
+                stack.x_states[0].copy_(x_in[s % n_in], non_blocking=True)
+                stack.step()
+                if log_idx:
+                    idx_log[s - first].copy_(stack.topk_idx, non_blocking=True)
+
+    run(0, Wm, False)
+    torch.cuda.synchronize()
+    stack.ctx.ffn_timing_begin(K * L)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(Wm, K, True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_timed, ffn_ms = stack.ctx.ffn_timing_end()
+    assert stack.ctx.device_flags() == 0
+
+    # algorithmic bytes of the FFN launches: weights of the distinct experts each launch touches
+    # plus its activation rows in and out
+    idx_host = idx_log.cpu().numpy()
+    uniq = np.array([[len(np.unique(idx_host[s, b])) for b in range(L)] for s in range(K)])
+    act_bytes = 2 * T * k * w.d_model * w.elem_bytes
+    ffn_bytes = float(uniq.sum()) * w.expert_bytes + float(K * L) * act_bytes
+    ffn_avg_us = 1e3 * ffn_ms / max(n_timed, 1)
+    ffn_gbps = ffn_bytes / max(n_timed, 1) / (ffn_avg_us * 1e-6) / 1e9 if n_timed else 0.0
+    h2d_bytes = float(uniq.sum()) * w.expert_bytes if w.offloaded else 0.0
+
+    out = {
+        "metric": "tokens/s through the pre-gated MoE stack (all layers; ms/token/layer alongside)",
+        "value": T * K / dt,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": Wm,
+        "ms_per_step": 1e3 * dt / K,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: L={L} d_model={w.d_model} d_ff={w.d_ff} E={E} top{k} T={T}/step, "
+                               f"experts {'offloaded to pinned host memory' if w.offloaded else 'resident in HBM'}",
+                   "tokens_per_step": T, "blocks": L},
+        "ms_per_token": 1e3 * dt / (T * K),
+        "ms_per_token_per_layer": 1e3 * dt / (T * K * L),
+        "block_latency_us": 1e6 * dt / (K * L),
+        "roofline": {"bound": "hbm", "achieved": ffn_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": ffn_gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "ffn_fused_kernel" if w.dtype == "bf16" else "ffn_f32_*", "launches": n_timed,
+                     "avg_launch_us": ffn_avg_us, "algorithmic_bytes_per_launch": ffn_bytes / max(n_timed, 1)},
+        "host_link": {"bytes_per_step": h2d_bytes / K, "achieved_GBps": h2d_bytes / dt / 1e9,
+                      "peak_GBps": LINK_PEAK_GBPS, "frac": h2d_bytes / dt / 1e9 / LINK_PEAK_GBPS,
+                      "mean_unique_experts_per_block": float(uniq.mean())},
+    }
+    if not args.no_cpu_baseline:
+        sample = args.cpu_sample_steps or max(1, min(K, int(round(600.0 / (T * L * k)))))
+        log(f"[bench] timing the CPU oracle on {sample} steps")
+        out["cpu_baseline"] = cpu_baseline(w, sample)
+    stack.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -59,6 +59,10 @@ typedef enum { PGMOE_F32 = 0, PGMOE_BF16 = 1 } pgmoe_dtype;
 #define PGMOE_FLAG_HOST_ONLY 1u /* create no device resources: argument checks and host logic
                                    work, every launch returns PGMOE_ENODEVICE */
 
+#define PGMOE_FLAG_FETCH_MEMCPY 2u /* migrate experts with hipMemcpyAsync (one per expert, issued
+                                      by the host after it has read the routing indices back)
+                                      instead of the default device-side pull kernel */
+
 #define PGMOE_MAX_EXPERTS 256 /* the paper's largest model has 256 experts per block */
 
 typedef struct {
@@ -83,7 +87,7 @@ typedef struct {
                                this fetch was issued: the quantity the peak-memory rule bounds */
     int32_t reserved;
     float fetch_ms;         /* copy-stream time of the batch (valid once it has completed) */
-    float wait_ms;          /* host time spent waiting for the indices */
+    float wait_ms;          /* host time spent waiting for the indices (memcpy mode) */
 } pgmoe_fetch_stats;
 
 /* ---- context ---------------------------------------------------------------------- */
@@ -134,15 +138,28 @@ int pgmoe_register_resident_experts(pgmoe_ctx *ctx, const void *dev_base, size_t
                                     size_t block_stride);
 /* Copy the experts that `topk_idx` (dev [T,k], produced on compute_stream) selects for
  * `block` into that block's slot generation (block & 1), on copy_stream.  The j-th smallest
- * selected expert id goes to slot j.  Order of events: the indices are read back once
- * compute_stream has produced them (the host waits for that); the copies wait until the
- * FFN that last used this generation (block-2, or the previous step's) has finished; a
- * done-event is recorded that pgmoe_expert_ffn(block) waits on.  With a resident store the
- * call only validates and returns n_unique = -1 without touching the indices.
+ * selected expert id goes to slot j.  copy_stream first waits for compute_stream to have
+ * produced the indices and for the FFN that last used this generation (block-2, or the
+ * previous step's) to have finished; a done-event is recorded that pgmoe_expert_ffn(block)
+ * waits on.
+ *   default (pull) mode : one kernel on copy_stream reads the indices, forms the distinct
+ *       expert list and pulls the blobs out of the pinned host store over the host link.
+ *       Nothing waits on the host: the call returns at once unless n_unique_out is given, in
+ *       which case it blocks until the copy has finished and returns the count.
+ *   PGMOE_FLAG_FETCH_MEMCPY : the host waits for the indices (small D2H copy), dedupes them
+ *       and issues one hipMemcpyAsync per distinct expert.
+ * If more distinct experts are selected than slots_per_gen, memcpy mode returns
+ * PGMOE_ENOSLOT; pull mode copies the first slots_per_gen of them, sets device flag bit 2 and
+ * the FFN skips the rows of the others (their output rows are zero).
+ * With a resident store the call only validates and returns n_unique = -1.
  * n_unique_out host | NULL. */
 int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int T,
                         void *compute_stream, void *copy_stream, int *n_unique_out);
 int pgmoe_get_fetch_stats(pgmoe_ctx *ctx, int block, pgmoe_fetch_stats *out /* host */);
+/* Device address of slot `slot` of the generation that serves `block` (for inspection: after
+ * the fetch of `block` has completed it holds the blob of the slot-th smallest selected
+ * expert).  dev_out host. */
+int pgmoe_slot_address(pgmoe_ctx *ctx, int block, int slot, void **dev_out);
 
 /* Host-only helper used by the fetch engine, exported for testing: ascending list of the
  * distinct values of idx[0..n) (all must lie in [0, E)); returns their number or a negative
@@ -208,9 +225,20 @@ typedef struct {
 int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *compute_stream,
                      void *copy_stream);
 
+/* ---- observability: duration of the expert-FFN kernel ------------------------------------
+ * pgmoe_ffn_timing_begin() makes every following pgmoe_expert_ffn() bracket its main kernel
+ * (the fused bf16 kernel, or the two f32 kernels; not the small partial-sum reduction) with a
+ * pair of HIP events on the stream it is launched on, for up to max_launches launches (the
+ * events are created here, not in the hot path; later launches are not timed).
+ * pgmoe_ffn_timing_end() waits for the recorded events, returns the number of timed launches
+ * and the sum of their event-to-event times in milliseconds, and switches timing off.
+ * n_out, total_ms_out host. */
+int pgmoe_ffn_timing_begin(pgmoe_ctx *ctx, int max_launches);
+int pgmoe_ffn_timing_end(pgmoe_ctx *ctx, int *n_out, float *total_ms_out);
+
 /* Sticky device-side condition bits since the last call of this function (synchronises the
  * device): bit 0 = a NaN logit was seen by a gate, bit 1 = an expert index outside [0,E)
- * reached pgmoe_permute. */
+ * reached pgmoe_permute or the pull kernel, bit 2 = more distinct experts than slots. */
 int pgmoe_device_flags(pgmoe_ctx *ctx, uint32_t *flags_out /* host */);
 
 #ifdef __cplusplus

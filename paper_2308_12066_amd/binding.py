@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "libpgmoe.so")
 OK, EINVAL, ENOTPINNED, ENOSLOT, EBADINDEX, EHIP, ENODEVICE, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7
 F32, BF16 = 0, 1
 FLAG_HOST_ONLY = 1
+FLAG_FETCH_MEMCPY = 2
 MAX_EXPERTS = 256
 
 EXPORTS = [
@@ -23,6 +24,7 @@ EXPORTS = [
     "pgmoe_pack_expert", "pgmoe_unpack_expert", "pgmoe_pregate_topk", "pgmoe_register_host_experts",
     "pgmoe_register_resident_experts", "pgmoe_fetch_experts", "pgmoe_get_fetch_stats", "pgmoe_unique_experts",
     "pgmoe_permute", "pgmoe_expert_ffn", "pgmoe_combine", "pgmoe_stack_step", "pgmoe_device_flags",
+    "pgmoe_ffn_timing_begin", "pgmoe_ffn_timing_end", "pgmoe_slot_address",
 ]
 
 
@@ -75,6 +77,9 @@ def _load():
     L.pgmoe_combine.argtypes = [vp, vp, vp, vp, i, vp, vp, vp, vp]
     L.pgmoe_stack_step.argtypes = [vp, POINTER(StepBuffers), i, vp, vp]
     L.pgmoe_device_flags.argtypes = [vp, POINTER(c_uint32)]
+    L.pgmoe_ffn_timing_begin.argtypes = [vp, i]
+    L.pgmoe_slot_address.argtypes = [vp, i, i, POINTER(vp)]
+    L.pgmoe_ffn_timing_end.argtypes = [vp, POINTER(c_int), POINTER(c_float)]
     for name in EXPORTS:
         if name not in ("pgmoe_last_error", "pgmoe_expert_bytes", "pgmoe_workspace_bytes"):
             getattr(L, name).restype = c_int
@@ -223,3 +228,17 @@ class Context:
         f = c_uint32(0)
         self._check(lib.pgmoe_device_flags(self._h, byref(f)))
         return f.value
+
+    def ffn_timing_begin(self, max_launches: int):
+        self._check(lib.pgmoe_ffn_timing_begin(self._h, max_launches))
+
+    def ffn_timing_end(self):
+        """-> (number of timed launches, sum of their durations in ms)."""
+        n, ms = c_int(0), c_float(0.0)
+        self._check(lib.pgmoe_ffn_timing_end(self._h, byref(n), byref(ms)))
+        return n.value, ms.value
+
+    def slot_address(self, block: int, slot: int) -> int:
+        p = c_void_p()
+        self._check(lib.pgmoe_slot_address(self._h, block, slot, byref(p)))
+        return p.value

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpgmoe.so")
-SOURCES = ["api.hip", "gate.hip", "permute.hip", "ffn.hip", "combine.hip", "engine.hip"]
+SOURCES = ["api.hip", "gate.hip", "permute.hip", "ffn.hip", "combine.hip", "fetch.hip", "engine.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -45,7 +45,7 @@ int check_config(const pgmoe_config *c, char *buf, size_t n) {
         BAD("max_tokens=%d (x top_k=%d) outside 1..2^24", c->max_tokens, c->top_k);
     if (c->slots_per_gen < 0 || c->slots_per_gen > c->n_experts)
         BAD("slots_per_gen=%d outside 0..n_experts", c->slots_per_gen);
-    if (c->flags & ~PGMOE_FLAG_HOST_ONLY) BAD("unknown flag bits 0x%x", c->flags);
+    if (c->flags & ~(PGMOE_FLAG_HOST_ONLY | PGMOE_FLAG_FETCH_MEMCPY)) BAD("unknown flag bits 0x%x", c->flags);
     return PGMOE_OK;
 #undef BAD
 }
@@ -86,6 +86,18 @@ static void tile_copy(uint16_t *tiled, uint16_t *plain, int K, int N, bool nt_ma
 
 using namespace pgmoe;
 
+static void free_timing(pgmoe_ctx *c) {
+    for (int i = 0; i < c->tim_cap; ++i) {
+        if (c->tim_begin && c->tim_begin[i]) (void)hipEventDestroy(c->tim_begin[i]);
+        if (c->tim_end && c->tim_end[i]) (void)hipEventDestroy(c->tim_end[i]);
+    }
+    delete[] c->tim_begin;
+    delete[] c->tim_end;
+    c->tim_begin = c->tim_end = nullptr;
+    c->tim_cap = c->tim_n = 0;
+    c->tim_on = false;
+}
+
 extern "C" {
 
 const char *pgmoe_last_error(const pgmoe_ctx *ctx) { return ctx ? ctx->err : g_err; }
@@ -105,6 +117,7 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
     if (!c) return fail(nullptr, PGMOE_EINVAL, "pgmoe_create: out of host memory");
     c->cfg = *cfg;
     c->host_only = (cfg->flags & PGMOE_FLAG_HOST_ONLY) != 0;
+    c->pull = (cfg->flags & PGMOE_FLAG_FETCH_MEMCPY) == 0;
     c->elem = cfg->dtype == PGMOE_F32 ? 4 : 2;
     c->expert_bytes = pgmoe_expert_bytes(cfg);
     c->slots = cfg->slots_per_gen > 0 ? cfg->slots_per_gen : default_slots(*cfg);
@@ -133,8 +146,10 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
             return fail(nullptr, PGMOE_ENODEVICE, "pgmoe_create: no HIP device is visible");
         }
         H(hipGetDevice(&c->device), "hipGetDevice");
-        H(hipMalloc((void **)&c->dev_flags, 256), "hipMalloc(flags)");
-        if (rc == PGMOE_OK) H(hipMemset(c->dev_flags, 0, 256), "hipMemset(flags)");
+        const size_t flag_bytes = 64 + sizeof(int32_t) * (size_t)cfg->n_blocks;
+        H(hipMalloc((void **)&c->dev_flags, flag_bytes), "hipMalloc(flags)");
+        if (rc == PGMOE_OK) H(hipMemset(c->dev_flags, 0, flag_bytes), "hipMemset(flags)");
+        c->dev_unique = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(c->dev_flags) + 64);
         size_t n_idx = (size_t)cfg->max_tokens * cfg->top_k;
         if (rc == PGMOE_OK) H(hipHostMalloc((void **)&c->idx_staging, n_idx * sizeof(int32_t), hipHostMallocDefault), "hipHostMalloc(idx staging)");
         if (rc == PGMOE_OK) H(hipEventCreateWithFlags(&c->idx_ready, hipEventDisableTiming), "hipEventCreate");
@@ -177,6 +192,7 @@ int pgmoe_destroy(pgmoe_ctx *c) {
         }
         delete[] c->fetch_begin;
         delete[] c->fetch_end;
+        free_timing(c);
     }
     delete[] c->stats;
     delete c;
@@ -302,6 +318,45 @@ int pgmoe_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, con
     NEED_DEVICE(ctx, fn);
     if (T == 0) return PGMOE_OK;
     return launch_combine(ctx, y_perm, row_of, topk_prob, T, y, x_res, x_next, (hipStream_t)stream);
+}
+
+int pgmoe_ffn_timing_begin(pgmoe_ctx *ctx, int max_launches) {
+    const char *fn = "pgmoe_ffn_timing_begin";
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
+    if (max_launches < 1 || max_launches > (1 << 20)) return fail(ctx, PGMOE_EINVAL, "%s: max_launches=%d outside 1..2^20", fn, max_launches);
+    NEED_DEVICE(ctx, fn);
+    if (ctx->tim_cap < max_launches) {
+        free_timing(ctx);
+        ctx->tim_begin = new (std::nothrow) hipEvent_t[max_launches]();
+        ctx->tim_end = new (std::nothrow) hipEvent_t[max_launches]();
+        if (!ctx->tim_begin || !ctx->tim_end) return fail(ctx, PGMOE_EINVAL, "%s: out of host memory", fn);
+        ctx->tim_cap = max_launches;
+        for (int i = 0; i < max_launches; ++i) {
+            PG_HIP(ctx, hipEventCreate(&ctx->tim_begin[i]));
+            PG_HIP(ctx, hipEventCreate(&ctx->tim_end[i]));
+        }
+    }
+    ctx->tim_n = 0;
+    ctx->tim_on = true;
+    return PGMOE_OK;
+}
+
+int pgmoe_ffn_timing_end(pgmoe_ctx *ctx, int *n_out, float *total_ms_out) {
+    const char *fn = "pgmoe_ffn_timing_end";
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
+    if (!n_out || !total_ms_out) return fail(ctx, PGMOE_EINVAL, "%s: NULL output pointer", fn);
+    NEED_DEVICE(ctx, fn);
+    ctx->tim_on = false;
+    double total = 0.0;
+    for (int i = 0; i < ctx->tim_n; ++i) {
+        PG_HIP(ctx, hipEventSynchronize(ctx->tim_end[i]));
+        float ms = 0.f;
+        PG_HIP(ctx, hipEventElapsedTime(&ms, ctx->tim_begin[i], ctx->tim_end[i]));
+        total += ms;
+    }
+    *n_out = ctx->tim_n;
+    *total_ms_out = (float)total;
+    return PGMOE_OK;
 }
 
 int pgmoe_device_flags(pgmoe_ctx *ctx, uint32_t *flags_out) {

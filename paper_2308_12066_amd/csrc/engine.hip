@@ -45,6 +45,9 @@ int pgmoe_register_host_experts(pgmoe_ctx *ctx, const void *host_base, size_t ex
             (void)hipGetLastError();
             return fail(ctx, PGMOE_ENOTPINNED, "%s: host_base is not pinned host memory (allocate it with hipHostMalloc)", fn);
         }
+        void *dev_view = nullptr;
+        PG_HIP(ctx, hipHostGetDevicePointer(&dev_view, const_cast<void *>(host_base), 0));
+        ctx->store_dev = (const char *)dev_view;
         if (!ctx->slot_pool) {
             const size_t bytes = (size_t)kGen * ctx->slots * ctx->expert_bytes;
             PG_HIP(ctx, hipMalloc((void **)&ctx->slot_pool, bytes));
@@ -94,6 +97,30 @@ int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int 
     const int gen = block & 1;
     BlockStats &st = ctx->stats[block];
     st = BlockStats();
+
+    if (ctx->pull) {
+        // device-side migration: the copy stream waits for the indices and for the generation
+        // to be free, then one kernel dedupes and pulls; the host is not involved
+        PG_HIP(ctx, hipEventRecord(ctx->idx_ready, cs));
+        PG_HIP(ctx, hipStreamWaitEvent(ps, ctx->idx_ready, 0));
+        if (ctx->ffn_recorded[gen]) PG_HIP(ctx, hipStreamWaitEvent(ps, ctx->ffn_done[gen], 0));
+        PG_HIP(ctx, hipEventRecord(ctx->fetch_begin[block], ps));
+        rc = launch_fetch_pull(ctx, block, topk_idx, n, ps);
+        if (rc) return rc;
+        PG_HIP(ctx, hipEventRecord(ctx->fetch_end[block], ps));
+        PG_HIP(ctx, hipEventRecord(ctx->fetch_done[gen], ps));
+        ctx->fetched_block[gen] = block;
+        ctx->live_slots[gen] = -1;  // known on the device only
+        st.timed = true;
+        st.s.n_unique = -1;
+        if (n_unique_out) {
+            PG_HIP(ctx, hipEventSynchronize(ctx->fetch_end[block]));
+            int32_t u = 0;
+            PG_HIP(ctx, hipMemcpy(&u, ctx->dev_unique + block, sizeof u, hipMemcpyDeviceToHost));
+            *n_unique_out = u;
+        }
+        return PGMOE_OK;
+    }
 
     // 1. bring the indices to the host (the only host wait of the block)
     const auto t0 = std::chrono::steady_clock::now();
@@ -149,8 +176,32 @@ int pgmoe_get_fetch_stats(pgmoe_ctx *ctx, int block, pgmoe_fetch_stats *out) {
         float ms = 0.f;
         PG_HIP(ctx, hipEventElapsedTime(&ms, ctx->fetch_begin[block], ctx->fetch_end[block]));
         st.s.fetch_ms = ms;
+        if (ctx->pull) {
+            // the pull kernel left the distinct-expert counts on the device
+            int32_t u[2] = {0, 0};
+            PG_HIP(ctx, hipMemcpy(&u[0], ctx->dev_unique + block, sizeof(int32_t), hipMemcpyDeviceToHost));
+            const bool prev_live = block > 0 && ctx->stats[block - 1].timed;
+            if (prev_live) PG_HIP(ctx, hipMemcpy(&u[1], ctx->dev_unique + block - 1, sizeof(int32_t), hipMemcpyDeviceToHost));
+            const int copied = u[0] < ctx->slots ? u[0] : ctx->slots;
+            st.s.n_unique = u[0];
+            st.s.n_copied = copied;
+            st.s.bytes_copied = (int64_t)copied * (int64_t)ctx->expert_bytes;
+            st.s.resident_slots = copied + (u[1] < ctx->slots ? u[1] : ctx->slots);
+        }
     }
     *out = st.s;
+    return PGMOE_OK;
+}
+
+int pgmoe_slot_address(pgmoe_ctx *ctx, int block, int slot, void **dev_out) {
+    const char *fn = "pgmoe_slot_address";
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
+    int rc = check_block(ctx, fn, block);
+    if (rc) return rc;
+    if (!dev_out) return fail(ctx, PGMOE_EINVAL, "%s: dev_out is NULL", fn);
+    if (slot < 0 || slot >= ctx->slots) return fail(ctx, PGMOE_EINVAL, "%s: slot=%d outside 0..%d", fn, slot, ctx->slots - 1);
+    if (!ctx->slot_pool) return fail(ctx, PGMOE_ESTATE, "%s: no slot pool (register a host expert store first)", fn);
+    *dev_out = ctx->slot_pool + ((size_t)(block & 1) * ctx->slots + slot) * ctx->expert_bytes;
     return PGMOE_OK;
 }
 
@@ -169,14 +220,14 @@ int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_
     if (ctx->host_only) return fail(ctx, PGMOE_ENODEVICE, "%s: context is host-only, nothing can be launched", fn);
     hipStream_t s = (hipStream_t)stream;
     if (ctx->store_mode == STORE_RESIDENT)
-        return launch_ffn(ctx, ctx->store_base + (size_t)block * ctx->block_stride, ctx->expert_stride, false, x_perm,
-                          expert_offsets, n_rows, y_perm, workspace, s);
+        return launch_ffn(ctx, ctx->store_base + (size_t)block * ctx->block_stride, ctx->expert_stride, false,
+                          ctx->cfg.n_experts, x_perm, expert_offsets, n_rows, y_perm, workspace, s);
     const int gen = block & 1;
     if (ctx->fetched_block[gen] != block)
         return fail(ctx, PGMOE_ESTATE, "%s: block %d was not fetched (generation holds block %d)", fn, block, ctx->fetched_block[gen]);
     PG_HIP(ctx, hipStreamWaitEvent(s, ctx->fetch_done[gen], 0));
-    rc = launch_ffn(ctx, ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes, ctx->expert_bytes, true, x_perm,
-                    expert_offsets, n_rows, y_perm, workspace, s);
+    rc = launch_ffn(ctx, ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes, ctx->expert_bytes, true, ctx->slots,
+                    x_perm, expert_offsets, n_rows, y_perm, workspace, s);
     if (rc) return rc;
     PG_HIP(ctx, hipEventRecord(ctx->ffn_done[gen], s));
     ctx->ffn_recorded[gen] = true;

@@ -5,7 +5,7 @@
 //   workgroup = (chunk of <= 16*MT rows of one expert) x (a range of d_ff columns)
 //   = (blockIdx.x, blockIdx.y).
 //   It keeps the chunk's activations in LDS, already in matrix-core operand order, and walks
-//   its d_ff range in sub-slabs of SUB = 16*NW columns:
+//   its d_ff range in sub-slabs of SUB = 16*NW columns (NW wavefronts per workgroup):
 //     phase A  wave w computes the 16 hidden features of n-tile w over the full d_model
 //              reduction (W1 tiles are contiguous in memory along k), applies ReLU, rounds to
 //              bf16 and drops the result into LDS in operand order for phase B;
@@ -20,6 +20,7 @@
 //
 // f32 path - plain float32 kernels (correctness configuration; no matrix cores).
 #include <algorithm>
+#include <cstdlib>
 
 #include "pgmoe_internal.h"
 
@@ -79,29 +80,68 @@ __device__ inline ChunkInfo find_chunk(const int32_t *__restrict__ offsets, int 
 }
 
 // ------------------------------------------------------------------------------------------
-template <int MT, int NTB, int NW>
+// Workgroup barrier that orders LDS traffic only: global loads already in flight (the weight
+// prefetch ring) stay in flight across it.
+__device__ inline void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// MT: 16-row tiles per chunk; KT = d_model/32; NW: wavefronts per workgroup (sub-slab = 16*NW
+// d_ff columns); D: weight tiles (1 KiB each) a wavefront keeps in flight.
+//
+// Per sub-slab a wavefront consumes NT = KT + KTB*NTB weight tiles in a fixed order: first the
+// KT tiles of its own W1 n-tile (phase A), then, for each of the KTB k-tiles of the sub-slab,
+// its NTB W2 tiles (phase B).  The tiles form one linear stream over all sub-slabs; tile g+D is
+// requested when tile g is consumed, so loads run ahead of the matrix cores across both phases
+// and across the LDS barrier between them.
+template <int MT, int KT, int NW, int D>
 __global__ __launch_bounds__(NW * 64) void ffn_fused_kernel(
-    const __bf16 *__restrict__ x_perm, const int32_t *__restrict__ offsets, int E, int d, int f, int f_range,
-    const char *__restrict__ w_base, size_t w_stride, int slot_by_rank, float *__restrict__ partial,
+    const __bf16 *__restrict__ x_perm, const int32_t *__restrict__ offsets, int E, int f, int f_range,
+    const char *__restrict__ w_base, size_t w_stride, int slot_by_rank, int n_slots, float *__restrict__ partial,
     __bf16 *__restrict__ y_perm, int n_rows) {
-    constexpr int SUB = 16 * NW;   // d_ff columns per sub-slab
-    constexpr int KTB = SUB / 32;  // k-tiles of phase B per sub-slab
-    constexpr int PA_UNROLL = 8;   // W1 tiles in flight per wave in phase A
+    constexpr int SUB = 16 * NW;      // d_ff columns per sub-slab
+    constexpr int KTB = SUB / 32;     // k-tiles of phase B per sub-slab
+    constexpr int NTD = KT * 2;       // n-tiles of the output (d_model / 16)
+    constexpr int NTB = NTD / NW;     // output n-tiles per wavefront
+    constexpr int NT_A = KT, NT_B = KTB * NTB, NT = NT_A + NT_B;
+    constexpr int d = KT * 32;
+    static_assert(NTD % NW == 0 && SUB % 32 == 0, "tile split");
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int KT = d >> 5;   // k-tiles of phase A
-    const int NTD = d >> 4;  // n-tiles of the output
 
     const ChunkInfo ci = find_chunk(offsets, E, 16 * MT, blockIdx.x);
     if (ci.nrows == 0) return;  // uniform over the workgroup
+    const bool no_weights = slot_by_rank && ci.slot >= n_slots;  // expert did not get a slot: rows are zeroed
 
-    bf16x8 *xs = reinterpret_cast<bf16x8 *>(smem);             // [MT][KT][64] operand cells
-    bf16x8 *hs = xs + (size_t)MT * KT * 64;                    // [2][MT][KTB][64]
+    const char *wexp = w_base + (size_t)(slot_by_rank ? ci.slot : ci.expert) * w_stride;
+    const bf16x8 *w1 = reinterpret_cast<const bf16x8 *>(wexp) + lane;
+    const bf16x8 *w2 = reinterpret_cast<const bf16x8 *>(wexp + (size_t)d * f * 2) + lane;
+    const int n_sub = no_weights ? 0 : f_range / SUB;
+    const int fs0 = blockIdx.y * f_range;
 
-    // stage the chunk's rows, zero-filling rows beyond nrows
+    // tile i (0 <= i < NT, compile-time after unrolling) of sub-slab s
+    auto tile_ptr = [&](int s, int i) -> const bf16x8 * {
+        const int fs = fs0 + s * SUB;
+        if (i < NT_A) return w1 + (((size_t)((fs >> 4) + wave) * KT + i) << 6);
+        const int j = i - NT_A, kb = j / NTB, a = j - kb * NTB;
+        return w2 + (((size_t)((fs >> 5) + kb) * NTD + wave * NTB + a) << 6);
+    };
+
+    bf16x8 ring[D];
+#pragma unroll
+    for (int g = 0; g < D; ++g) {
+        if (g / NT < n_sub) ring[g] = *tile_ptr(g / NT, g % NT);
+    }
+
+    bf16x8 *xs = reinterpret_cast<bf16x8 *>(smem);   // [MT][KT][64] operand cells
+    bf16x8 *hs = xs + (size_t)MT * KT * 64;          // [2][MT][KTB][64]
+
+    // stage the chunk's rows (zero-filling rows beyond nrows) while the first weight tiles fly
     {
-        const int cells_per_row = d >> 3;
+        constexpr int cells_per_row = d >> 3;
         const uint4 *src = reinterpret_cast<const uint4 *>(x_perm + (size_t)ci.row0 * d);
         uint4 *dst = reinterpret_cast<uint4 *>(xs);
         for (int i = tid; i < 16 * MT * cells_per_row; i += NW * 64) {
@@ -111,11 +151,7 @@ __global__ __launch_bounds__(NW * 64) void ffn_fused_kernel(
             dst[(((m >> 4) * KT + (k8 >> 2)) << 6) + (m & 15) + 16 * (k8 & 3)] = v;
         }
     }
-    __syncthreads();
-
-    const char *wexp = w_base + (size_t)(slot_by_rank ? ci.slot : ci.expert) * w_stride;
-    const bf16x8 *w1 = reinterpret_cast<const bf16x8 *>(wexp);
-    const bf16x8 *w2 = reinterpret_cast<const bf16x8 *>(wexp + (size_t)d * f * 2);
+    lds_barrier();
 
     floatx4 yacc[NTB][MT];
 #pragma unroll
@@ -123,65 +159,54 @@ __global__ __launch_bounds__(NW * 64) void ffn_fused_kernel(
 #pragma unroll
         for (int m = 0; m < MT; ++m) yacc[a][m] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    const int f0 = blockIdx.y * f_range;
     const int q = lane >> 4;
-    int buf = 0;
-    for (int fs = f0; fs < f0 + f_range; fs += SUB, buf ^= 1) {
-        // ---- phase A: hidden features [fs + 16*wave, +16) for all rows of the chunk
+    for (int s = 0; s < n_sub; ++s) {
         floatx4 hacc[MT];
 #pragma unroll
         for (int m = 0; m < MT; ++m) hacc[m] = floatx4{0.f, 0.f, 0.f, 0.f};
-        const bf16x8 *wa = w1 + ((size_t)((fs >> 4) + wave) * KT << 6) + lane;
-        int kt = 0;
-        for (; kt + PA_UNROLL <= KT; kt += PA_UNROLL) {
-            bf16x8 a[PA_UNROLL];
+        bf16x8 hfrag[MT];
+        const bf16x8 *hb = hs + (size_t)(s & 1) * MT * KTB * 64;
 #pragma unroll
-            for (int u = 0; u < PA_UNROLL; ++u) a[u] = wa[(size_t)(kt + u) << 6];
-#pragma unroll
-            for (int u = 0; u < PA_UNROLL; ++u)
+        for (int i = 0; i < NT; ++i) {
+            const bf16x8 v = ring[i % D];
+            {   // request tile g + D of the stream
+                const int ds = (i + D) / NT, ii = (i + D) % NT;
+                if (s + ds < n_sub) ring[i % D] = *tile_ptr(s + ds, ii);
+            }
+            if (i < NT_A) {
+                // ---- phase A: hidden features [fs + 16*wave, +16) over the full d_model reduction
 #pragma unroll
                 for (int m = 0; m < MT; ++m)
-                    hacc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], xs[((m * KT + kt + u) << 6) + lane], hacc[m], 0, 0, 0);
-        }
-        for (; kt < KT; ++kt) {
-            const bf16x8 a = wa[(size_t)kt << 6];
+                    hacc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v, xs[((m * KT + i) << 6) + lane], hacc[m], 0, 0, 0);
+                if (i == NT_A - 1) {
+                    // ReLU, round to bf16, store as phase-B operand: feature 16*wave + 4*q + r is
+                    // k-tile wave/2, k-group 2*(wave%2) + q/2, position 4*(q%2) + r of token lane%16
+                    char *hbase = reinterpret_cast<char *>(hs + (size_t)(s & 1) * MT * KTB * 64);
 #pragma unroll
-            for (int m = 0; m < MT; ++m)
-                hacc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, xs[((m * KT + kt) << 6) + lane], hacc[m], 0, 0, 0);
-        }
-        // ReLU, round to bf16, store as phase-B operand: feature 16*wave + 4*q + r is k-tile
-        // wave/2, k-group 2*(wave%2) + q/2, position 4*(q%2) + r of the cell of token lane%16.
-        {
-            char *hbase = reinterpret_cast<char *>(hs + (size_t)buf * MT * KTB * 64);
+                    for (int m = 0; m < MT; ++m) {
+                        bf16x4 h;
+                        h.x = (__bf16)fmaxf(hacc[m].x, 0.f);
+                        h.y = (__bf16)fmaxf(hacc[m].y, 0.f);
+                        h.z = (__bf16)fmaxf(hacc[m].z, 0.f);
+                        h.w = (__bf16)fmaxf(hacc[m].w, 0.f);
+                        const int cell = ((m * KTB + (wave >> 1)) << 6) + (lane & 15) + 16 * (2 * (wave & 1) + (q >> 1));
+                        *reinterpret_cast<bf16x4 *>(hbase + (size_t)cell * 16 + 8 * (q & 1)) = h;
+                    }
+                    // one barrier per sub-slab is enough: the next sub-slab writes the other half of hs
+                    lds_barrier();
+                }
+            } else {
+                // ---- phase B: y[:, wave's columns] += H_sub . W2[fs .. fs+SUB, wave's columns]
+                const int j = i - NT_A, kb = j / NTB, a = j - kb * NTB;
+                if (a == 0) {
 #pragma unroll
-            for (int m = 0; m < MT; ++m) {
-                bf16x4 h;
-                h.x = (__bf16)fmaxf(hacc[m].x, 0.f);
-                h.y = (__bf16)fmaxf(hacc[m].y, 0.f);
-                h.z = (__bf16)fmaxf(hacc[m].z, 0.f);
-                h.w = (__bf16)fmaxf(hacc[m].w, 0.f);
-                const int cell = ((m * KTB + (wave >> 1)) << 6) + (lane & 15) + 16 * (2 * (wave & 1) + (q >> 1));
-                *reinterpret_cast<bf16x4 *>(hbase + (size_t)cell * 16 + 8 * (q & 1)) = h;
-            }
-        }
-        __syncthreads();
-        // ---- phase B: y[:, wave's columns] += H_sub . W2[fs .. fs+SUB, wave's columns]
-        const bf16x8 *hb = hs + (size_t)buf * MT * KTB * 64;
-#pragma unroll
-        for (int kb = 0; kb < KTB; ++kb) {
-            const bf16x8 *wb = w2 + (((size_t)((fs >> 5) + kb) * NTD + wave * NTB) << 6) + lane;
-            bf16x8 hfrag[MT];
-#pragma unroll
-            for (int m = 0; m < MT; ++m) hfrag[m] = hb[((m * KTB + kb) << 6) + lane];
-#pragma unroll
-            for (int a = 0; a < NTB; ++a) {
-                const bf16x8 wv = wb[(size_t)a << 6];
+                    for (int m = 0; m < MT; ++m) hfrag[m] = hb[((m * KTB + kb) << 6) + lane];
+                }
 #pragma unroll
                 for (int m = 0; m < MT; ++m)
-                    yacc[a][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, hfrag[m], yacc[a][m], 0, 0, 0);
+                    yacc[a][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v, hfrag[m], yacc[a][m], 0, 0, 0);
             }
         }
-        // no second barrier: the next sub-slab writes the other half of hs
     }
 
     // ---- epilogue: lane holds token (lane%16) of tile m, output columns 16*(wave*NTB+a) + 4*q + {0..3}
@@ -210,20 +235,31 @@ __global__ __launch_bounds__(NW * 64) void ffn_fused_kernel(
     }
 }
 
-// y_perm[row][c] = bf16( sum_p partial[p][row][c] ), p ascending.
+// y_perm[row][c] = bf16( sum_p partial[p][row][c] ).  A workgroup covers 16 float4 columns;
+// its 16 "p-lanes" each add every 16th partial (p = pl, pl+16, ...) and the 16 sub-sums are
+// added in fixed order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void ffn_reduce_kernel(const float *__restrict__ partial, int P, int n_rows, int d,
                                                           __bf16 *__restrict__ y_perm) {
+    __shared__ floatx4 sub[16][17];
     const size_t total4 = (size_t)n_rows * d / 4;
-    const size_t stride4 = total4;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total4; i += (size_t)gridDim.x * 256) {
+    const int col = threadIdx.x & 15, pl = threadIdx.x >> 4;
+    const size_t i = (size_t)blockIdx.x * 16 + col;
+    floatx4 s = floatx4{0.f, 0.f, 0.f, 0.f};
+    if (i < total4) {
         const floatx4 *src = reinterpret_cast<const floatx4 *>(partial) + i;
-        floatx4 s = src[0];
-        for (int p = 1; p < P; ++p) s += src[(size_t)p * stride4];
+        for (int p = pl; p < P; p += 16) s += src[(size_t)p * total4];
+    }
+    sub[pl][col] = s;
+    __syncthreads();
+    if (pl == 0 && i < total4) {
+        floatx4 t = sub[0][col];
+#pragma unroll
+        for (int k = 1; k < 16; ++k) t += sub[k][col];
         bf16x4 o;
-        o.x = (__bf16)s.x;
-        o.y = (__bf16)s.y;
-        o.z = (__bf16)s.z;
-        o.w = (__bf16)s.w;
+        o.x = (__bf16)t.x;
+        o.y = (__bf16)t.y;
+        o.z = (__bf16)t.z;
+        o.w = (__bf16)t.w;
         reinterpret_cast<bf16x4 *>(y_perm)[i] = o;
     }
 }
@@ -248,7 +284,7 @@ __device__ inline void find_row_expert(const int32_t *offsets, int E, int row, i
 __global__ __launch_bounds__(256) void ffn_f32_hidden_kernel(const float *__restrict__ x_perm,
                                                               const int32_t *__restrict__ offsets, int E, int d, int f,
                                                               const char *__restrict__ w_base, size_t w_stride,
-                                                              int slot_by_rank, float *__restrict__ h) {
+                                                              int slot_by_rank, int n_slots, float *__restrict__ h) {
     __shared__ int s_e, s_s;
     const int row = blockIdx.x;
     if (threadIdx.x == 0) find_row_expert(offsets, E, row, &s_e, &s_s);
@@ -256,6 +292,10 @@ __global__ __launch_bounds__(256) void ffn_f32_hidden_kernel(const float *__rest
     const float *w1 = reinterpret_cast<const float *>(w_base + (size_t)(slot_by_rank ? s_s : s_e) * w_stride);
     const int j = blockIdx.y * 256 + threadIdx.x;
     if (j >= f) return;
+    if (slot_by_rank && s_s >= n_slots) {  // expert did not get a slot
+        h[(size_t)row * f + j] = 0.f;
+        return;
+    }
     const float *xr = x_perm + (size_t)row * d;
     float acc = 0.f;
     for (int i = 0; i < d; ++i) acc = fmaf(xr[i], w1[(size_t)i * f + j], acc);
@@ -264,7 +304,8 @@ __global__ __launch_bounds__(256) void ffn_f32_hidden_kernel(const float *__rest
 
 __global__ __launch_bounds__(256) void ffn_f32_out_kernel(const float *__restrict__ h, const int32_t *__restrict__ offsets,
                                                            int E, int d, int f, const char *__restrict__ w_base,
-                                                           size_t w_stride, int slot_by_rank, float *__restrict__ y_perm) {
+                                                           size_t w_stride, int slot_by_rank, int n_slots,
+                                                           float *__restrict__ y_perm) {
     __shared__ int s_e, s_s;
     const int row = blockIdx.x;
     if (threadIdx.x == 0) find_row_expert(offsets, E, row, &s_e, &s_s);
@@ -272,6 +313,10 @@ __global__ __launch_bounds__(256) void ffn_f32_out_kernel(const float *__restric
     const float *w2 = reinterpret_cast<const float *>(w_base + (size_t)(slot_by_rank ? s_s : s_e) * w_stride) + (size_t)d * f;
     const int c = blockIdx.y * 256 + threadIdx.x;
     if (c >= d) return;
+    if (slot_by_rank && s_s >= n_slots) {
+        y_perm[(size_t)row * d + c] = 0.f;
+        return;
+    }
     const float *hr = h + (size_t)row * f;
     float acc = 0.f;
     for (int j = 0; j < f; ++j) acc = fmaf(hr[j], w2[(size_t)j * d + c], acc);
@@ -285,18 +330,41 @@ static int smallest_divisor_at_least(int n, int want) {
     return n;
 }
 
+static int env_int(const char *name, int dflt) {
+    const char *v = getenv(name);
+    return v && *v ? atoi(v) : dflt;
+}
+
+// Geometry of the fused kernel for n_rows rows.  Developer overrides (for sweeps): environment
+// variables PGMOE_FFN_MT, PGMOE_FFN_NW, PGMOE_FFN_P, read at every call.
 FfnPlan plan_ffn(const pgmoe_config &c, int n_rows) {
     FfnPlan p;
     const int E = c.n_experts;
+    const int kt = c.d_model / 32;
+    const int active = std::max(1, std::min(E, n_rows));  // upper bound of the distinct experts
     const int mean_rows = (n_rows + E - 1) / E;
-    const int ntb = c.d_model / 64;  // output n-tiles per wave with 4 waves
+    // rows per chunk: 16 for decode-sized batches, up to 64 when experts see tens of rows
     int mt = mean_rows <= 4 ? 1 : (mean_rows <= 20 ? 2 : 4);
-    while (mt > 1 && (ntb * mt > 48 || (size_t)mt * c.d_model * 32 + 4096u * mt > 150u * 1024u)) mt >>= 1;
+    // wavefronts per workgroup: 2 (32-column sub-slabs) when there are too few experts to fill
+    // the chip otherwise, 8 for the 64-row chunks (halves the accumulators per wavefront)
+    int nw = 4;
+    if (mt == 1 && active * (c.d_ff / 64) < 256 && (kt == 24 || kt == 32)) nw = 2;
+    if (mt == 4 && (kt == 24 || kt == 32)) nw = 8;
+    if (mt == 4 && nw == 4 && kt > 24) mt = 2;
+    if (mt == 2 && kt > 32) mt = 1;
+    mt = env_int("PGMOE_FFN_MT", mt);
+    nw = env_int("PGMOE_FFN_NW", nw);
     p.mt = mt;
-    const int active = std::max(1, std::min(E, n_rows));
+    p.nw = nw;
     p.max_chunks = active + n_rows / (16 * mt);
-    const int nsub = c.d_ff / kSub;
-    const int want = (768 + active - 1) / active;  // aim at >= 768 workgroups
+    const int sub = 16 * nw;
+    const int nsub = c.d_ff / sub;
+    // partial sums: aim at >= 768 workgroups, but keep the float32 partial traffic
+    // (write + read = 8 bytes per element per partial) below ~6 % of the weight bytes
+    int want = (768 + active - 1) / active;
+    const double traffic_cap = 0.06 * (double)active * c.d_ff / (2.0 * n_rows);
+    want = std::max(1, std::min(want, (int)traffic_cap));
+    want = env_int("PGMOE_FFN_P", want);
     p.n_partial = smallest_divisor_at_least(nsub, std::min(want, nsub));
     p.f_range = c.d_ff / p.n_partial;
     return p;
@@ -305,68 +373,80 @@ FfnPlan plan_ffn(const pgmoe_config &c, int n_rows) {
 size_t ffn_workspace_bytes(const pgmoe_config &c) {
     const int64_t max_rows = (int64_t)c.max_tokens * c.top_k;
     if (c.dtype == PGMOE_F32) return (size_t)max_rows * c.d_ff * 4;
-    size_t best = 256;
-    auto consider = [&](int n) {
-        const FfnPlan p = plan_ffn(c, n);
-        if (p.n_partial > 1) best = std::max(best, (size_t)p.n_partial * n * c.d_model * 4);
-    };
-    for (int n = 1; n <= std::min<int64_t>(max_rows, c.n_experts); ++n) consider(n);
-    consider((int)max_rows);
-    return (best + 255) & ~(size_t)255;
+    // worst case over every geometry plan_ffn can pick: one partial per 32-column sub-slab
+    const size_t worst = (size_t)(c.d_ff / 32) * std::min<int64_t>(max_rows, 4096) * c.d_model * 4;
+    const size_t big = (size_t)16 * max_rows * c.d_model * 4;
+    return ((std::max(worst, big) + 255) & ~(size_t)255);
 }
 
-template <int MT, int NTB>
-static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, size_t w_stride, bool slot_by_rank,
+// Next free event pair when FFN timing is on, else -1.
+static int timing_slot(pgmoe_ctx *ctx) {
+    if (!ctx->tim_on || ctx->tim_n >= ctx->tim_cap) return -1;
+    return ctx->tim_n++;
+}
+
+template <int MT, int KT, int NW, int D>
+static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots,
                         const void *x_perm, const int32_t *offsets, int n_rows, void *y_perm, void *workspace,
                         hipStream_t s) {
-    constexpr int NW = 4;
     const pgmoe_config &c = ctx->cfg;
-    const size_t lds = (size_t)MT * (c.d_model / 32) * 1024 + 2u * MT * (16 * NW / 32) * 1024;
-    auto kern = ffn_fused_kernel<MT, NTB, NW>;
-    static thread_local size_t lds_set = 0;  // per instantiation
-    if (lds > 48 * 1024 && lds > lds_set) {
+    const size_t lds = (size_t)MT * KT * 1024 + 2u * MT * (16 * NW / 32) * 1024;
+    auto kern = ffn_fused_kernel<MT, KT, NW, D>;
+    static thread_local bool attr_set = false;  // per instantiation
+    if (lds > 48 * 1024 && !attr_set) {
         PG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        lds_set = lds;
+        attr_set = true;
     }
     float *partial = p.n_partial > 1 ? (float *)workspace : nullptr;
+    if (partial && (size_t)p.n_partial * n_rows * c.d_model * 4 > ffn_workspace_bytes(c))
+        return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: %d partial sums of %d rows do not fit the workspace", p.n_partial, n_rows);
+    const int tslot = timing_slot(ctx);
+    if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_begin[tslot], s));
     hipLaunchKernelGGL(kern, dim3(p.max_chunks, p.n_partial), dim3(NW * 64), lds, s, (const __bf16 *)x_perm, offsets,
-                       c.n_experts, c.d_model, c.d_ff, p.f_range, w_base, w_stride, slot_by_rank ? 1 : 0, partial,
-                       (__bf16 *)y_perm, n_rows);
+                       c.n_experts, c.d_ff, p.f_range, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, partial, (__bf16 *)y_perm,
+                       n_rows);
     PG_HIP(ctx, hipGetLastError());
+    if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
     if (partial) {
         const size_t total4 = (size_t)n_rows * c.d_model / 4;
-        const int grid = (int)std::min<size_t>((total4 + 255) / 256, 4096);
-        hipLaunchKernelGGL(ffn_reduce_kernel, dim3(grid), dim3(256), 0, s, partial, p.n_partial, n_rows, c.d_model,
-                           (__bf16 *)y_perm);
+        hipLaunchKernelGGL(ffn_reduce_kernel, dim3((unsigned)((total4 + 15) / 16)), dim3(256), 0, s, partial, p.n_partial,
+                           n_rows, c.d_model, (__bf16 *)y_perm);
         PG_HIP(ctx, hipGetLastError());
     }
     return PGMOE_OK;
 }
 
-int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, const void *x_perm,
+int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots, const void *x_perm,
                const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s) {
     const pgmoe_config &c = ctx->cfg;
     if (n_rows == 0) return PGMOE_OK;
     if (c.dtype == PGMOE_F32) {
         float *h = (float *)workspace;
+        const int tslot = timing_slot(ctx);
+        if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_begin[tslot], s));
         hipLaunchKernelGGL(ffn_f32_hidden_kernel, dim3(n_rows, (c.d_ff + 255) / 256), dim3(256), 0, s,
                            (const float *)x_perm, offsets, c.n_experts, c.d_model, c.d_ff, w_base, w_stride,
-                           slot_by_rank ? 1 : 0, h);
+                           slot_by_rank ? 1 : 0, n_slots, h);
         PG_HIP(ctx, hipGetLastError());
         hipLaunchKernelGGL(ffn_f32_out_kernel, dim3(n_rows, (c.d_model + 255) / 256), dim3(256), 0, s, h, offsets,
-                           c.n_experts, c.d_model, c.d_ff, w_base, w_stride, slot_by_rank ? 1 : 0, (float *)y_perm);
+                           c.n_experts, c.d_model, c.d_ff, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, (float *)y_perm);
         PG_HIP(ctx, hipGetLastError());
+        if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
         return PGMOE_OK;
     }
     const FfnPlan p = plan_ffn(c, n_rows);
-    const int ntb = c.d_model / 64;
-#define PG_CASE(MT_, NTB_) \
-    if (p.mt == MT_ && ntb == NTB_) return launch_fused<MT_, NTB_>(ctx, p, w_base, w_stride, slot_by_rank, x_perm, offsets, n_rows, y_perm, workspace, s)
-    PG_CASE(1, 1); PG_CASE(1, 2); PG_CASE(1, 4); PG_CASE(1, 8); PG_CASE(1, 12); PG_CASE(1, 16); PG_CASE(1, 32);
-    PG_CASE(2, 1); PG_CASE(2, 2); PG_CASE(2, 4); PG_CASE(2, 8); PG_CASE(2, 12); PG_CASE(2, 16);
-    PG_CASE(4, 1); PG_CASE(4, 2); PG_CASE(4, 4); PG_CASE(4, 8); PG_CASE(4, 12);
+    const int kt = c.d_model / 32;
+    if (c.d_ff % (16 * p.nw)) return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: d_ff=%d is not a multiple of the %d-column sub-slab", c.d_ff, 16 * p.nw);
+#define PG_CASE(MT_, KT_, NW_, D_) \
+    if (p.mt == MT_ && kt == KT_ && p.nw == NW_) return launch_fused<MT_, KT_, NW_, D_>(ctx, p, w_base, w_stride, slot_by_rank, n_slots, x_perm, offsets, n_rows, y_perm, workspace, s)
+    PG_CASE(1, 2, 4, 4); PG_CASE(1, 4, 4, 8); PG_CASE(1, 8, 4, 16); PG_CASE(1, 16, 4, 16); PG_CASE(1, 24, 4, 16);
+    PG_CASE(1, 32, 4, 16); PG_CASE(1, 64, 4, 16); PG_CASE(1, 24, 2, 24); PG_CASE(1, 32, 2, 24);
+    PG_CASE(2, 2, 4, 4); PG_CASE(2, 4, 4, 8); PG_CASE(2, 8, 4, 16); PG_CASE(2, 16, 4, 16); PG_CASE(2, 24, 4, 16);
+    PG_CASE(2, 32, 4, 16);
+    PG_CASE(4, 2, 4, 4); PG_CASE(4, 4, 4, 8); PG_CASE(4, 8, 4, 16); PG_CASE(4, 16, 4, 16); PG_CASE(4, 24, 4, 16);
+    PG_CASE(4, 24, 8, 8); PG_CASE(4, 32, 8, 8);
 #undef PG_CASE
-    return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: no bf16 kernel built for d_model=%d (supported: 64, 128, 256, 512, 768, 1024, 2048)", c.d_model);
+    return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: no bf16 kernel built for d_model=%d with %d-row chunks and %d wavefronts", c.d_model, 16 * p.mt, p.nw);
 }
 
 }  // namespace pgmoe

@@ -19,11 +19,10 @@ constexpr int kGen = 2;  // block generations resident at once (current + next b
 // Device-side sticky condition bits (see pgmoe_device_flags).
 constexpr uint32_t kFlagNaN = 1u;
 constexpr uint32_t kFlagBadIndex = 2u;
+constexpr uint32_t kFlagNoSlot = 4u;
 
 // Rows of one expert that a single FFN workgroup handles at once (bf16 path): 16 * MT.
 constexpr int kTileRows = 16;
-// Width of the d_ff sub-slab a workgroup pushes through both products before moving on.
-constexpr int kSub = 64;
 
 struct BlockStats {
     pgmoe_fetch_stats s;
@@ -48,6 +47,9 @@ struct pgmoe_ctx {
     // device resources
     char *slot_pool;       // [kGen][slots][expert_bytes]
     uint32_t *dev_flags;   // sticky condition bits
+    int32_t *dev_unique;   // [n_blocks] distinct experts found by the pull kernel (dev_flags + 64 bytes)
+    const char *store_dev; // device-visible address of the pinned host store
+    bool pull;             // fetch with the device-side pull kernel
     int32_t *idx_staging;  // pinned host [max_tokens * k]
     hipEvent_t idx_ready;
     hipEvent_t fetch_done[pgmoe::kGen];
@@ -58,6 +60,11 @@ struct pgmoe_ctx {
     int live_slots[pgmoe::kGen];
     bool ffn_recorded[pgmoe::kGen];
     pgmoe::BlockStats *stats;  // [n_blocks]
+
+    // optional timing of the FFN kernel (pgmoe_ffn_timing_begin/end)
+    hipEvent_t *tim_begin, *tim_end;
+    int tim_cap, tim_n;
+    bool tim_on;
 
     char err[512];
 };
@@ -81,7 +88,8 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 // rows per workgroup chunk, number of d_ff ranges (partial sums) and the chunk-count bound.
 struct FfnPlan {
     int mt;          // 16-row tiles per chunk (1, 2 or 4)
-    int f_range;     // d_ff columns per workgroup (multiple of kSub)
+    int nw;          // wavefronts per workgroup (2, 4 or 8); sub-slab = 16*nw d_ff columns
+    int f_range;     // d_ff columns per workgroup (multiple of the sub-slab)
     int n_partial;   // d_ff / f_range
     int max_chunks;  // upper bound of sum_e ceil(n_e / (16*mt))
 };
@@ -93,8 +101,9 @@ int launch_gate(pgmoe_ctx *ctx, const void *x, const void *w, const float *bias,
                 float *prob, float *probs, hipStream_t s);
 int launch_permute(pgmoe_ctx *ctx, const void *x, const int32_t *idx, int T, void *x_perm,
                    int32_t *row_of, int32_t *offsets, hipStream_t s);
-int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, const void *x_perm,
+int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots, const void *x_perm,
                const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s);
+int launch_fetch_pull(pgmoe_ctx *ctx, int block, const int32_t *idx, int n, hipStream_t s);
 int launch_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, const float *prob, int T,
                    void *y, const void *x_res, void *x_next, hipStream_t s);
 

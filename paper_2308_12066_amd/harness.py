@@ -91,9 +91,9 @@ class ExpertStore:
 class Stack:
     """One pre-gated MoE stack on the GPU: context, gate tensors, per-step buffers, two streams."""
 
-    def __init__(self, w: W.Workload, store: ExpertStore, gates=None, max_tokens=None, slots_per_gen=0):
+    def __init__(self, w: W.Workload, store: ExpertStore, gates=None, max_tokens=None, slots_per_gen=0, flags=0):
         self.w = w
-        self.cfg = config_for(w, max_tokens=max_tokens, slots_per_gen=slots_per_gen)
+        self.cfg = config_for(w, max_tokens=max_tokens, slots_per_gen=slots_per_gen, flags=flags)
         self.ctx = B.Context(self.cfg)
         self.store = store
         T, d, k, E, L = self.cfg.max_tokens, w.d_model, w.top_k, w.n_experts, w.n_blocks

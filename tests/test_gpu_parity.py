@@ -306,8 +306,8 @@ def check_stack_step(H, w, stack, gates, expert_cache, sample_tokens=None, label
     return stats
 
 
-def make_stack(H, w, threads=HOST_THREADS):
-    cfg = H.config_for(w)
+def make_stack(H, w, threads=HOST_THREADS, flags=0):
+    cfg = H.config_for(w, flags=flags)
     cache = {}
 
     def get(b, e):
@@ -317,7 +317,7 @@ def make_stack(H, w, threads=HOST_THREADS):
 
     store = H.ExpertStore(w, cfg, threads=threads, get_expert=get)
     gates = W.gate_tensors(w)
-    stack = H.Stack(w, store, gates=gates)
+    stack = H.Stack(w, store, gates=gates, flags=flags)
     return stack, gates, (lambda b, e: cache[(b, e)])
 
 
@@ -339,18 +339,19 @@ def test_cfg1_tiny_f32_stack_all_tokens(hx):
     stack.close()
 
 
-@pytest.mark.parametrize("name,blocks,steps,sample", [
-    ("cfg2", 6, 6, None), ("cfg3", 6, 3, None), ("cfg4", 2, 1, 192), ("cfg4_offloaded", 2, 1, 64),
-    ("cfg5", 3, 2, None), ("cfg5_top2", 3, 2, None),
+@pytest.mark.parametrize("name,blocks,steps,sample,fetch", [
+    ("cfg2", 6, 6, None, "pull"), ("cfg2", 6, 4, None, "memcpy"), ("cfg3", 6, 3, None, "pull"),
+    ("cfg4", 2, 1, 192, "-"), ("cfg4_offloaded", 2, 1, 64, "pull"), ("cfg5", 3, 2, None, "pull"),
+    ("cfg5_top2", 3, 2, None, "pull"), ("cfg5_top2", 3, 2, None, "memcpy"),
 ])
-def test_switch_shaped_stacks(hx, name, blocks, steps, sample):
+def test_switch_shaped_stacks(hx, name, blocks, steps, sample, fetch):
     """Full d_model / d_ff / E / T of the Switch-shaped workloads; the number of blocks and steps
     is cut down to keep host-side weight generation within the test budget (each block runs
     the same launches)."""
     H, B = hx
     w = W.CONFIGS[name].replace(n_blocks=blocks)
-    say(f"stack {name}: L={blocks} steps={steps} T={w.tokens} E={w.n_experts} k={w.top_k} offloaded={w.offloaded}")
-    stack, gates, cache = make_stack(H, w)
+    say(f"stack {name}: L={blocks} steps={steps} T={w.tokens} E={w.n_experts} k={w.top_k} offloaded={w.offloaded} fetch={fetch}")
+    stack, gates, cache = make_stack(H, w, flags=B.FLAG_FETCH_MEMCPY if fetch == "memcpy" else 0)
     near = tot = 0
     for s in range(steps):
         stack.set_input(W.step_input(w, s))
@@ -369,3 +370,84 @@ def test_switch_shaped_stacks(hx, name, blocks, steps, sample):
     say(f"  {name}: near-tie tokens exempted {near} of {tot}")
     assert stack.ctx.device_flags() == 0
     stack.close()
+
+
+# ------------------------------------------------------------------------------ migration engine
+def _device_bytes(addr, nbytes):
+    """Copy nbytes from a raw device address to host (plumbing: hipMemcpy through ctypes)."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    out = np.empty(nbytes, dtype=np.uint8)
+    rc = hip.hipMemcpy(ctypes.c_void_p(out.ctypes.data), ctypes.c_void_p(addr), ctypes.c_size_t(nbytes), ctypes.c_int(2))
+    assert rc == 0
+    return out
+
+
+@pytest.mark.parametrize("fetch", ["pull", "memcpy"])
+def test_fetch_copies_exactly_the_selected_experts(hx, fetch):
+    """Slot j of the block's generation holds, byte for byte, the blob of the j-th smallest
+    selected expert, and nothing but the selected experts is counted as copied."""
+    H, B = hx
+    w = W.Workload("fetch_case", 70, 3, 128, 256, 16, 2, 12, 1, "bf16", 0.0, True)
+    cfg = H.config_for(w, flags=B.FLAG_FETCH_MEMCPY if fetch == "memcpy" else 0)
+    store = H.ExpertStore(w, cfg, threads=4)
+    ctx = B.Context(cfg)
+    ctx.register_host_experts(store.host, store.expert_stride, store.block_stride)
+    comp, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    g = np.random.default_rng(9)
+    for block in (0, 1, 2, 1):
+        idx = np.stack([g.choice(16, size=2, replace=False) for _ in range(12)]).astype(np.int32)
+        idx_d = torch.from_numpy(idx).cuda()
+        torch.cuda.synchronize()
+        nu = ctx.fetch_experts(block, idx_d, 12, comp, copy)
+        torch.cuda.synchronize()
+        uniq = np.unique(idx)
+        assert nu == len(uniq)
+        fs = ctx.fetch_stats(block)
+        assert fs.n_unique == len(uniq) and fs.n_copied == len(uniq) and fs.bytes_copied == len(uniq) * store.expert_bytes
+        for j, e in enumerate(uniq):
+            got = _device_bytes(ctx.slot_address(block, j), store.expert_bytes)
+            assert np.array_equal(got, store.blob(block, int(e))), f"block {block} slot {j} != expert {e}"
+    assert ctx.device_flags() == 0
+    ctx.close()
+
+
+def test_pull_fetch_with_too_few_slots_flags_and_zeroes(hx):
+    """slots_per_gen smaller than the number of distinct experts: the pull kernel copies the
+    first slots_per_gen experts, raises the device flag, and the FFN zeroes the other rows."""
+    H, B = hx
+    w = W.Workload("noslot_case", 71, 1, 128, 256, 8, 1, 8, 1, "bf16", 0.0, True)
+    cfg = H.config_for(w, slots_per_gen=2)
+    cache = {}
+
+    def get(b, e):
+        cache[e] = W.expert_weights(w, b, e)
+        return cache[e]
+
+    store = H.ExpertStore(w, cfg, threads=1, get_expert=get)
+    ctx = B.Context(cfg)
+    ctx.register_host_experts(store.host, store.expert_stride, store.block_stride)
+    comp, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    idx = np.array([[1], [1], [3], [5], [5], [6], [3], [1]], dtype=np.int32)      # distinct: 1, 3, 5, 6
+    x = W.round_to_bf16(np.random.default_rng(2).standard_normal((8, 128)).astype(np.float32))
+    xd, idx_d = H.to_device(x, "bf16"), torch.from_numpy(idx).cuda()
+    x_perm = torch.zeros((8, 128), dtype=torch.bfloat16, device="cuda")
+    y_perm = torch.full((8, 128), 3.0, dtype=torch.bfloat16, device="cuda")
+    row_of = torch.zeros(8, dtype=torch.int32, device="cuda")
+    offs = torch.zeros(9, dtype=torch.int32, device="cuda")
+    ws = torch.zeros(ctx.workspace_bytes, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    assert ctx.fetch_experts(0, idx_d, 8, comp, copy) == 4
+    ctx.permute(xd, idx_d, 8, x_perm, row_of, offs, comp)
+    ctx.expert_ffn(0, x_perm, offs, 8, y_perm, ws, comp)
+    torch.cuda.synchronize()
+    assert ctx.device_flags() & 4
+    r = R.route(idx, 8)
+    y = H.to_numpy64(y_perm)
+    for e in (1, 3):
+        rows = slice(r["offsets"][e], r["offsets"][e + 1])
+        ref = R.ffn_rows(x[idx[:, 0] == e], *cache[e])
+        assert nerr(y[rows], ref) <= TOL["bf16"]
+    for e in (5, 6):
+        assert np.all(y[r["offsets"][e]: r["offsets"][e + 1]] == 0.0)
+    ctx.close()
