@@ -86,7 +86,7 @@ typedef struct {
     int32_t resident_slots; /* slots holding live experts over both generations right after
                                this fetch was issued: the quantity the peak-memory rule bounds */
     int32_t reserved;
-    float fetch_ms;         /* copy-stream time of the batch (valid once it has completed) */
+    float fetch_ms;         /* copy-stream time of the batch; 0 unless pgmoe_fetch_timing() is on */
     float wait_ms;          /* host time spent waiting for the indices (memcpy mode) */
 } pgmoe_fetch_stats;
 
@@ -137,11 +137,13 @@ int pgmoe_register_host_experts(pgmoe_ctx *ctx, const void *host_base, size_t ex
 int pgmoe_register_resident_experts(pgmoe_ctx *ctx, const void *dev_base, size_t expert_stride,
                                     size_t block_stride);
 /* Copy the experts that `topk_idx` (dev [T,k], produced on compute_stream) selects for
- * `block` into that block's slot generation (block & 1), on copy_stream.  The j-th smallest
- * selected expert id goes to slot j.  copy_stream first waits for compute_stream to have
- * produced the indices and for the FFN that last used this generation (block-2, or the
- * previous step's) to have finished; a done-event is recorded that pgmoe_expert_ffn(block)
- * waits on.
+ * `block` into that block's slot generation (block & 1).  The j-th smallest selected expert
+ * id goes to slot j.  Even blocks are copied on copy_stream, odd blocks on a second copy
+ * stream the context owns (so consecutive blocks' migrations do not queue behind each other);
+ * passing copy_stream == compute_stream instead runs the copy in plain stream order on
+ * compute_stream (an exposed fetch, as block 0's).  The copy first waits for compute_stream to
+ * have produced the indices and for the FFN that last used this generation (block-2, or the
+ * previous step's) to have finished; pgmoe_expert_ffn(block) waits for the copy.
  *   default (pull) mode : one kernel on copy_stream reads the indices, forms the distinct
  *       expert list and pulls the blobs out of the pinned host store over the host link.
  *       Nothing waits on the host: the call returns at once unless n_unique_out is given, in
@@ -156,6 +158,10 @@ int pgmoe_register_resident_experts(pgmoe_ctx *ctx, const void *dev_base, size_t
 int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int T,
                         void *compute_stream, void *copy_stream, int *n_unique_out);
 int pgmoe_get_fetch_stats(pgmoe_ctx *ctx, int block, pgmoe_fetch_stats *out /* host */);
+/* Bracket every following fetch with a pair of timing events on the copy stream (fetch_ms of
+ * pgmoe_fetch_stats).  Off by default: each event record costs microseconds between the
+ * migration kernels of consecutive blocks. */
+int pgmoe_fetch_timing(pgmoe_ctx *ctx, int enable);
 /* Device address of slot `slot` of the generation that serves `block` (for inspection: after
  * the fetch of `block` has completed it holds the blob of the slot-th smallest selected
  * expert).  dev_out host. */

@@ -24,7 +24,7 @@ EXPORTS = [
     "pgmoe_pack_expert", "pgmoe_unpack_expert", "pgmoe_pregate_topk", "pgmoe_register_host_experts",
     "pgmoe_register_resident_experts", "pgmoe_fetch_experts", "pgmoe_get_fetch_stats", "pgmoe_unique_experts",
     "pgmoe_permute", "pgmoe_expert_ffn", "pgmoe_combine", "pgmoe_stack_step", "pgmoe_device_flags",
-    "pgmoe_ffn_timing_begin", "pgmoe_ffn_timing_end", "pgmoe_slot_address",
+    "pgmoe_ffn_timing_begin", "pgmoe_ffn_timing_end", "pgmoe_slot_address", "pgmoe_fetch_timing",
 ]
 
 
@@ -78,6 +78,7 @@ def _load():
     L.pgmoe_stack_step.argtypes = [vp, POINTER(StepBuffers), i, vp, vp]
     L.pgmoe_device_flags.argtypes = [vp, POINTER(c_uint32)]
     L.pgmoe_ffn_timing_begin.argtypes = [vp, i]
+    L.pgmoe_fetch_timing.argtypes = [vp, i]
     L.pgmoe_slot_address.argtypes = [vp, i, i, POINTER(vp)]
     L.pgmoe_ffn_timing_end.argtypes = [vp, POINTER(c_int), POINTER(c_float)]
     for name in EXPORTS:
@@ -242,3 +243,6 @@ class Context:
         p = c_void_p()
         self._check(lib.pgmoe_slot_address(self._h, block, slot, byref(p)))
         return p.value
+
+    def fetch_timing(self, enable: bool):
+        self._check(lib.pgmoe_fetch_timing(self._h, 1 if enable else 0))

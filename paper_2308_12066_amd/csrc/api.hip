@@ -153,9 +153,11 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
         size_t n_idx = (size_t)cfg->max_tokens * cfg->top_k;
         if (rc == PGMOE_OK) H(hipHostMalloc((void **)&c->idx_staging, n_idx * sizeof(int32_t), hipHostMallocDefault), "hipHostMalloc(idx staging)");
         if (rc == PGMOE_OK) H(hipEventCreateWithFlags(&c->idx_ready, hipEventDisableTiming), "hipEventCreate");
+        if (rc == PGMOE_OK) H(hipStreamCreateWithFlags(&c->copy2, hipStreamNonBlocking), "hipStreamCreate");
         for (int g = 0; g < kGen && rc == PGMOE_OK; ++g) {
-            H(hipEventCreateWithFlags(&c->fetch_done[g], hipEventDisableTiming), "hipEventCreate");
-            H(hipEventCreateWithFlags(&c->ffn_done[g], hipEventDisableTiming), "hipEventCreate");
+            // these two only order device work against device work: no host-visible release needed
+            H(hipEventCreateWithFlags(&c->fetch_done[g], hipEventDisableTiming | hipEventReleaseToDevice), "hipEventCreate");
+            H(hipEventCreateWithFlags(&c->ffn_done[g], hipEventDisableTiming | hipEventReleaseToDevice), "hipEventCreate");
         }
         if (rc == PGMOE_OK) {
             c->fetch_begin = new (std::nothrow) hipEvent_t[cfg->n_blocks]();
@@ -182,6 +184,7 @@ int pgmoe_destroy(pgmoe_ctx *c) {
         if (c->dev_flags) (void)hipFree(c->dev_flags);
         if (c->idx_staging) (void)hipHostFree(c->idx_staging);
         if (c->idx_ready) (void)hipEventDestroy(c->idx_ready);
+        if (c->copy2) (void)hipStreamDestroy(c->copy2);
         for (int g = 0; g < kGen; ++g) {
             if (c->fetch_done[g]) (void)hipEventDestroy(c->fetch_done[g]);
             if (c->ffn_done[g]) (void)hipEventDestroy(c->ffn_done[g]);

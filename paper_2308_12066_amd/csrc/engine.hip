@@ -4,8 +4,13 @@
 // picked block N+1's experts, only those are copied to the GPU while block N executes, and
 // the GPU holds the activated experts of two consecutive blocks at most.  Here that is a
 // slot pool of two generations (generation = block & 1).  Read-after-write: the FFN of a
-// block waits on the generation's fetch_done event.  Write-after-read: a fetch into a
-// generation waits on the ffn_done event of the block that used it last.
+// block waits on the generation's fetch_done event (unless the fetch ran on the FFN's own
+// stream).  Write-after-read: a fetch into a generation must not start before the FFN that
+// read it last has finished; the indices the fetch depends on are produced on the compute
+// stream after that FFN, so waiting for them covers it, and only when the FFN ran on some
+// other stream is an extra event recorded there (at fetch time, behind the FFN) and waited on.
+// Odd generations are fetched on an internal second copy stream, so the migration of block
+// i+1 does not queue behind that of block i: the host link stays busy across the hand-over.
 #include <chrono>
 
 #include "pgmoe_internal.h"
@@ -22,6 +27,18 @@ int check_store_args(pgmoe_ctx *ctx, const char *fn, const void *base, size_t ex
         return fail(ctx, PGMOE_EINVAL, "%s: expert_stride=%zu must be a multiple of 256 and >= %zu", fn, expert_stride, ctx->expert_bytes);
     if (block_stride < expert_stride * (size_t)ctx->cfg.n_experts || block_stride % 256)
         return fail(ctx, PGMOE_EINVAL, "%s: block_stride=%zu must be a multiple of 256 and >= n_experts*expert_stride", fn, block_stride);
+    return PGMOE_OK;
+}
+
+// Make `ps` wait for the FFN that last read generation `gen`.  Work already queued on `cs`
+// precedes the indices this fetch waits for, so an FFN on `cs` (or on `ps` itself) needs
+// nothing; an FFN on any other stream gets an event recorded behind it now.
+int wait_for_last_reader(pgmoe_ctx *ctx, int gen, hipStream_t cs, hipStream_t ps) {
+    if (!ctx->ffn_recorded[gen]) return PGMOE_OK;
+    const hipStream_t fs = ctx->ffn_stream[gen];
+    if (fs == cs || fs == ps) return PGMOE_OK;
+    PG_HIP(ctx, hipEventRecord(ctx->ffn_done[gen], fs));
+    PG_HIP(ctx, hipStreamWaitEvent(ps, ctx->ffn_done[gen], 0));
     return PGMOE_OK;
 }
 
@@ -90,31 +107,36 @@ int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int 
         return PGMOE_OK;
     }
     if (ctx->host_only) return fail(ctx, PGMOE_ENODEVICE, "%s: context is host-only, nothing can be launched", fn);
-    if (copy_stream == compute_stream) return fail(ctx, PGMOE_EINVAL, "%s: copy_stream must differ from compute_stream", fn);
-
     hipStream_t cs = (hipStream_t)compute_stream, ps = (hipStream_t)copy_stream;
     const int n = T * ctx->cfg.top_k;
     const int gen = block & 1;
+    const bool inline_fetch = ps == cs;  // exposed fetch on the compute stream itself: plain stream order
+    if (!inline_fetch && gen == 1) ps = ctx->copy2;
     BlockStats &st = ctx->stats[block];
     st = BlockStats();
 
     if (ctx->pull) {
         // device-side migration: the copy stream waits for the indices and for the generation
         // to be free, then one kernel dedupes and pulls; the host is not involved
-        PG_HIP(ctx, hipEventRecord(ctx->idx_ready, cs));
-        PG_HIP(ctx, hipStreamWaitEvent(ps, ctx->idx_ready, 0));
-        if (ctx->ffn_recorded[gen]) PG_HIP(ctx, hipStreamWaitEvent(ps, ctx->ffn_done[gen], 0));
-        PG_HIP(ctx, hipEventRecord(ctx->fetch_begin[block], ps));
+        if (!inline_fetch) {
+            PG_HIP(ctx, hipEventRecord(ctx->idx_ready, cs));
+            PG_HIP(ctx, hipStreamWaitEvent(ps, ctx->idx_ready, 0));
+        }
+        rc = wait_for_last_reader(ctx, gen, cs, ps);
+        if (rc) return rc;
+        if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_begin[block], ps));
         rc = launch_fetch_pull(ctx, block, topk_idx, n, ps);
         if (rc) return rc;
-        PG_HIP(ctx, hipEventRecord(ctx->fetch_end[block], ps));
-        PG_HIP(ctx, hipEventRecord(ctx->fetch_done[gen], ps));
+        if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_end[block], ps));
+        if (!inline_fetch) PG_HIP(ctx, hipEventRecord(ctx->fetch_done[gen], ps));
+        ctx->fetch_stream[gen] = ps;
         ctx->fetched_block[gen] = block;
         ctx->live_slots[gen] = -1;  // known on the device only
-        st.timed = true;
+        st.timed = ctx->fetch_timing;
+        st.pulled = true;
         st.s.n_unique = -1;
         if (n_unique_out) {
-            PG_HIP(ctx, hipEventSynchronize(ctx->fetch_end[block]));
+            PG_HIP(ctx, hipStreamSynchronize(ps));
             int32_t u = 0;
             PG_HIP(ctx, hipMemcpy(&u, ctx->dev_unique + block, sizeof u, hipMemcpyDeviceToHost));
             *n_unique_out = u;
@@ -141,19 +163,21 @@ int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int 
     if (nu > ctx->slots) return fail(ctx, PGMOE_ENOSLOT, "%s: %d distinct experts selected but only %d slots per generation", fn, nu, ctx->slots);
 
     // 3. the generation may still be read by the FFN that used it last
-    if (ctx->ffn_recorded[gen]) PG_HIP(ctx, hipStreamWaitEvent(ps, ctx->ffn_done[gen], 0));
-    PG_HIP(ctx, hipEventRecord(ctx->fetch_begin[block], ps));
+    rc = wait_for_last_reader(ctx, gen, cs, ps);
+    if (rc) return rc;
+    if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_begin[block], ps));
     char *gen_base = ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes;
     const char *src_block = ctx->store_base + (size_t)block * ctx->block_stride;
     for (int j = 0; j < nu; ++j)
         PG_HIP(ctx, hipMemcpyAsync(gen_base + (size_t)j * ctx->expert_bytes, src_block + (size_t)uniq[j] * ctx->expert_stride,
                                    ctx->expert_bytes, hipMemcpyHostToDevice, ps));
-    PG_HIP(ctx, hipEventRecord(ctx->fetch_end[block], ps));
-    PG_HIP(ctx, hipEventRecord(ctx->fetch_done[gen], ps));
+    if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_end[block], ps));
+    if (!inline_fetch) PG_HIP(ctx, hipEventRecord(ctx->fetch_done[gen], ps));
 
+    ctx->fetch_stream[gen] = ps;
     ctx->fetched_block[gen] = block;
     ctx->live_slots[gen] = nu;
-    st.timed = true;
+    st.timed = ctx->fetch_timing;
     st.s.n_unique = nu;
     st.s.n_copied = nu;
     st.s.bytes_copied = (int64_t)nu * (int64_t)ctx->expert_bytes;
@@ -171,16 +195,19 @@ int pgmoe_get_fetch_stats(pgmoe_ctx *ctx, int block, pgmoe_fetch_stats *out) {
     if (rc) return rc;
     if (!out) return fail(ctx, PGMOE_EINVAL, "%s: out is NULL", fn);
     BlockStats &st = ctx->stats[block];
-    if (st.timed && !ctx->host_only) {
-        PG_HIP(ctx, hipEventSynchronize(ctx->fetch_end[block]));
-        float ms = 0.f;
-        PG_HIP(ctx, hipEventElapsedTime(&ms, ctx->fetch_begin[block], ctx->fetch_end[block]));
-        st.s.fetch_ms = ms;
-        if (ctx->pull) {
+    if (!ctx->host_only) {
+        if (st.timed) {
+            PG_HIP(ctx, hipEventSynchronize(ctx->fetch_end[block]));
+            float ms = 0.f;
+            PG_HIP(ctx, hipEventElapsedTime(&ms, ctx->fetch_begin[block], ctx->fetch_end[block]));
+            st.s.fetch_ms = ms;
+        }
+        if (st.pulled) {
             // the pull kernel left the distinct-expert counts on the device
+            PG_HIP(ctx, hipStreamSynchronize(ctx->fetch_stream[block & 1]));
             int32_t u[2] = {0, 0};
             PG_HIP(ctx, hipMemcpy(&u[0], ctx->dev_unique + block, sizeof(int32_t), hipMemcpyDeviceToHost));
-            const bool prev_live = block > 0 && ctx->stats[block - 1].timed;
+            const bool prev_live = block > 0 && ctx->stats[block - 1].pulled;
             if (prev_live) PG_HIP(ctx, hipMemcpy(&u[1], ctx->dev_unique + block - 1, sizeof(int32_t), hipMemcpyDeviceToHost));
             const int copied = u[0] < ctx->slots ? u[0] : ctx->slots;
             st.s.n_unique = u[0];
@@ -190,6 +217,12 @@ int pgmoe_get_fetch_stats(pgmoe_ctx *ctx, int block, pgmoe_fetch_stats *out) {
         }
     }
     *out = st.s;
+    return PGMOE_OK;
+}
+
+int pgmoe_fetch_timing(pgmoe_ctx *ctx, int enable) {
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "pgmoe_fetch_timing: ctx is NULL");
+    ctx->fetch_timing = enable != 0;
     return PGMOE_OK;
 }
 
@@ -225,12 +258,12 @@ int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_
     const int gen = block & 1;
     if (ctx->fetched_block[gen] != block)
         return fail(ctx, PGMOE_ESTATE, "%s: block %d was not fetched (generation holds block %d)", fn, block, ctx->fetched_block[gen]);
-    PG_HIP(ctx, hipStreamWaitEvent(s, ctx->fetch_done[gen], 0));
+    if (ctx->fetch_stream[gen] != s) PG_HIP(ctx, hipStreamWaitEvent(s, ctx->fetch_done[gen], 0));
     rc = launch_ffn(ctx, ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes, ctx->expert_bytes, true, ctx->slots,
                     x_perm, expert_offsets, n_rows, y_perm, workspace, s);
     if (rc) return rc;
-    PG_HIP(ctx, hipEventRecord(ctx->ffn_done[gen], s));
     ctx->ffn_recorded[gen] = true;
+    ctx->ffn_stream[gen] = s;
     return PGMOE_OK;
 }
 
@@ -261,7 +294,8 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     // block 0: its own (conventional) gate, then an exposed fetch
     rc = pgmoe_pregate_topk(ctx, x_at(0), io->gate_w[0], bias_at(0), T, idx_at(0), prob_at(0), nullptr, compute_stream);
     if (rc) return rc;
-    rc = pgmoe_fetch_experts(ctx, 0, idx_at(0), T, compute_stream, copy_stream, nullptr);
+    // (nothing can overlap it, so it runs on the compute stream itself: no cross-stream hand-over)
+    rc = pgmoe_fetch_experts(ctx, 0, idx_at(0), T, compute_stream, ctx->pull ? compute_stream : copy_stream, nullptr);
     if (rc) return rc;
 
     for (int i = 0; i < L; ++i) {

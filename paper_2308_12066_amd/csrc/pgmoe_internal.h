@@ -26,7 +26,8 @@ constexpr int kTileRows = 16;
 
 struct BlockStats {
     pgmoe_fetch_stats s;
-    bool timed;  // fetch_begin/fetch_end were recorded for this block
+    bool timed;   // fetch_begin/fetch_end were recorded for this block
+    bool pulled;  // fetched by the pull kernel: counts live on the device
 };
 
 }  // namespace pgmoe
@@ -59,6 +60,10 @@ struct pgmoe_ctx {
     int fetched_block[pgmoe::kGen];  // block whose experts the generation holds (-1: none)
     int live_slots[pgmoe::kGen];
     bool ffn_recorded[pgmoe::kGen];
+    hipStream_t ffn_stream[pgmoe::kGen];    // stream the generation's last FFN ran on
+    hipStream_t fetch_stream[pgmoe::kGen];  // stream the generation's last fetch ran on
+    hipStream_t copy2;                      // internal copy stream for odd generations
+    bool fetch_timing;               // record fetch_begin / fetch_end
     pgmoe::BlockStats *stats;  // [n_blocks]
 
     // optional timing of the FFN kernel (pgmoe_ffn_timing_begin/end)

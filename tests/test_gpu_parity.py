@@ -352,6 +352,7 @@ def test_switch_shaped_stacks(hx, name, blocks, steps, sample, fetch):
     w = W.CONFIGS[name].replace(n_blocks=blocks)
     say(f"stack {name}: L={blocks} steps={steps} T={w.tokens} E={w.n_experts} k={w.top_k} offloaded={w.offloaded} fetch={fetch}")
     stack, gates, cache = make_stack(H, w, flags=B.FLAG_FETCH_MEMCPY if fetch == "memcpy" else 0)
+    stack.ctx.fetch_timing(True)
     near = tot = 0
     for s in range(steps):
         stack.set_input(W.step_input(w, s))
