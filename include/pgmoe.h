@@ -138,8 +138,9 @@ int pgmoe_register_resident_experts(pgmoe_ctx *ctx, const void *dev_base, size_t
                                     size_t block_stride);
 /* Copy the experts that `topk_idx` (dev [T,k], produced on compute_stream) selects for
  * `block` into that block's slot generation (block & 1).  The j-th smallest selected expert
- * id goes to slot j.  Even blocks are copied on copy_stream, odd blocks on a second copy
- * stream the context owns (so consecutive blocks' migrations do not queue behind each other);
+ * id goes to slot j.  Blocks 0, 1 and the odd blocks are copied on copy_stream, even blocks
+ * from 2 on on a second copy stream the context owns (so that consecutive blocks' migrations
+ * do not queue behind each other);
  * passing copy_stream == compute_stream instead runs the copy in plain stream order on
  * compute_stream (an exposed fetch, as block 0's).  The copy first waits for compute_stream to
  * have produced the indices and for the FFN that last used this generation (block-2, or the
@@ -208,7 +209,7 @@ int pgmoe_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, con
 
 /* ---- a-6: one pass of the whole stack (Sec. IV-B wiring + Sec. IV-C overlap) ------------
  * Runs blocks 0..L-1 for one batch of T tokens:
- *   block 0   : conventional gate on x_0 -> fetch(0) (exposed) ; pre-gate 0 on x_0 -> fetch(1)
+ *   block 0   : conventional gate and pre-gate 0 on x_0 -> fetch(0) (exposed), fetch(1) behind it
  *   block i   : [pre-gate i on x_i -> fetch(i+1) on the copy stream]  ||  permute, FFN_i,
  *               combine on the compute stream, x_{i+1} = x_i + y_i
  *   block L-1 : no gate.

@@ -9,8 +9,9 @@
 // read it last has finished; the indices the fetch depends on are produced on the compute
 // stream after that FFN, so waiting for them covers it, and only when the FFN ran on some
 // other stream is an extra event recorded there (at fetch time, behind the FFN) and waited on.
-// Odd generations are fetched on an internal second copy stream, so the migration of block
-// i+1 does not queue behind that of block i: the host link stays busy across the hand-over.
+// Even blocks from block 2 on are fetched on an internal second copy stream, so the migration
+// of block i+1 does not queue behind that of block i: the host link stays busy across the
+// hand-over (two pull kernels share the link while they overlap).
 #include <chrono>
 
 #include "pgmoe_internal.h"
@@ -111,7 +112,7 @@ int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int 
     const int n = T * ctx->cfg.top_k;
     const int gen = block & 1;
     const bool inline_fetch = ps == cs;  // exposed fetch on the compute stream itself: plain stream order
-    if (!inline_fetch && gen == 1) ps = ctx->copy2;
+    if (!inline_fetch && gen == 0 && block > 1) ps = ctx->copy2;  // blocks 0,1 queue on the caller's stream, then alternate
     BlockStats &st = ctx->stats[block];
     st = BlockStats();
 
@@ -291,16 +292,25 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     auto bias_at = [&](int g) -> const float * { return io->gate_b ? io->gate_b[g] : nullptr; };
     int rc;
 
-    // block 0: its own (conventional) gate, then an exposed fetch
+    // Block 0: its own (conventional) gate and, on the same input, pre-gate 0 for block 1.  Both
+    // routings are known before anything can execute, so block 0's exposed fetch and block 1's
+    // fetch are queued back to back on the copy stream: the link never idles between them.
     rc = pgmoe_pregate_topk(ctx, x_at(0), io->gate_w[0], bias_at(0), T, idx_at(0), prob_at(0), nullptr, compute_stream);
     if (rc) return rc;
-    // (nothing can overlap it, so it runs on the compute stream itself: no cross-stream hand-over)
-    rc = pgmoe_fetch_experts(ctx, 0, idx_at(0), T, compute_stream, ctx->pull ? compute_stream : copy_stream, nullptr);
+    if (L > 1) {
+        rc = pgmoe_pregate_topk(ctx, x_at(0), io->gate_w[1], bias_at(1), T, idx_at(1), prob_at(1), nullptr, compute_stream);
+        if (rc) return rc;
+    }
+    rc = pgmoe_fetch_experts(ctx, 0, idx_at(0), T, compute_stream, copy_stream, nullptr);
     if (rc) return rc;
+    if (L > 1) {
+        rc = pgmoe_fetch_experts(ctx, 1, idx_at(1), T, compute_stream, copy_stream, nullptr);
+        if (rc) return rc;
+    }
 
     for (int i = 0; i < L; ++i) {
         // pre-gate of block i routes block i+1; its experts start moving before block i executes
-        if (i + 1 < L) {
+        if (i > 0 && i + 1 < L) {
             rc = pgmoe_pregate_topk(ctx, x_at(i), io->gate_w[i + 1], bias_at(i + 1), T, idx_at(i + 1), prob_at(i + 1), nullptr,
                                     compute_stream);
             if (rc) return rc;

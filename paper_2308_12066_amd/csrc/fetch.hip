@@ -5,15 +5,17 @@
 // scans the routing indices into an LDS presence table, derives the ascending list of
 // distinct experts (slot j <- j-th of them, the same rule the FFN uses to find its weights)
 // and then pulls its share of the selected blobs straight out of the pinned host store with
-// 16-byte loads over the host link.  A handful of workgroups saturates the link, so the grid
-// is kept small and leaves the compute units to the block that is executing.
+// 16-byte loads over the host link.  Host-link reads in flight slow down every concurrent HBM
+// access on this chip (a 9.4 MB read kernel goes from 2.9 us to 7/9/12/30 us with 64/96/128/512
+// KiB of pull loads outstanding), so the grid keeps just enough in flight to saturate the link:
+// 24 workgroups x 4 wavefronts x one 1 KiB load each (96 KiB: 56.3 of 57 GB/s).
 #include "pgmoe_internal.h"
 
 namespace pgmoe {
 
 constexpr int FETCH_THREADS = 256;
-constexpr int FETCH_GRID = 16;
-constexpr int FETCH_UNROLL = 8;
+constexpr int FETCH_GRID = 24;
+constexpr int FETCH_UNROLL = 1;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 

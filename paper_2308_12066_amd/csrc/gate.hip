@@ -2,11 +2,12 @@
 // (Sec. II-B: the gate gives every expert a probability per token and the best ones are
 // activated; Sec. IV-B: the same function, placed in block N, routes block N+1).
 //
-// One workgroup handles GATE_TB tokens.  The token rows are staged in LDS as float32 in
-// chunks of GATE_DC features; thread (g, e) owns expert column e and every G-th feature
-// row, so a wavefront reads W in contiguous runs.  The G partial sums per (token, expert)
-// are added in fixed order (bit-reproducible), then one wavefront per token does the
-// softmax and k rounds of arg-max with DPP-free shuffles.
+// One workgroup handles a few tokens.  The token rows are staged in LDS as float32 in chunks of
+// GATE_DC features; the threads split W by expert columns and feature rows, accumulate in
+// float32 and fold their partial sums in a fixed order (bit-reproducible); then one wavefront
+// per token does the softmax and k rounds of arg-max with shuffles.  Two kernels: a vectorised
+// one for power-of-two expert counts (every configuration of the paper) and a scalar one for
+// any other E.
 #include "pgmoe_internal.h"
 
 namespace pgmoe {
@@ -31,55 +32,12 @@ __device__ inline void wave_argmax(float &v, int &i) {
     }
 }
 
-template <typename XT>
-__global__ __launch_bounds__(GATE_THREADS) void gate_topk_kernel(
-    const XT *__restrict__ x, const XT *__restrict__ w, const float *__restrict__ bias, int T, int d, int E, int k,
-    int32_t *__restrict__ idx_out, float *__restrict__ prob_out, float *__restrict__ probs_out, uint32_t *flags) {
-    __shared__ float xs[GATE_TB * GATE_DC];
-    __shared__ float part[GATE_THREADS * GATE_TB];  // [G][TB][E], G*E <= 256
-    __shared__ float zs[GATE_TB * PGMOE_MAX_EXPERTS];
-
+// Softmax over the E logits of each token and k rounds of arg-max (ties to the lowest index,
+// NaN ranks as -infinity and raises the NaN flag).  zs: LDS [tokens][PGMOE_MAX_EXPERTS] logits.
+// One wavefront per token; a lane holds experts lane, lane+64, lane+128, lane+192.
+__device__ inline void softmax_topk(const float *zs, int t0, int nt, int E, int k, int32_t *__restrict__ idx_out,
+                                    float *__restrict__ prob_out, float *__restrict__ probs_out, uint32_t *flags) {
     const int tid = threadIdx.x;
-    const int t0 = blockIdx.x * GATE_TB;
-    const int nt = min(GATE_TB, T - t0);
-    const int G = GATE_THREADS / E;
-    const int g = tid / E, e = tid - g * E;
-    const bool active = g < G;
-
-    float acc[GATE_TB];
-#pragma unroll
-    for (int t = 0; t < GATE_TB; ++t) acc[t] = 0.f;
-
-    for (int c0 = 0; c0 < d; c0 += GATE_DC) {
-        const int dc = min(GATE_DC, d - c0);
-        __syncthreads();
-        for (int i = tid; i < GATE_TB * dc; i += GATE_THREADS) {
-            const int t = i / dc, c = i - t * dc;
-            xs[t * GATE_DC + c] = t < nt ? to_float(x[(size_t)(t0 + t) * d + c0 + c]) : 0.f;
-        }
-        __syncthreads();
-        if (active) {
-            for (int i = g; i < dc; i += G) {
-                const float wv = to_float(w[(size_t)(c0 + i) * E + e]);
-#pragma unroll
-                for (int t = 0; t < GATE_TB; ++t) acc[t] = fmaf(xs[t * GATE_DC + i], wv, acc[t]);
-            }
-        }
-    }
-    if (active) {
-#pragma unroll
-        for (int t = 0; t < GATE_TB; ++t) part[(g * GATE_TB + t) * E + e] = acc[t];
-    }
-    __syncthreads();
-    for (int o = tid; o < GATE_TB * E; o += GATE_THREADS) {
-        const int t = o / E, ee = o - t * E;
-        float s = 0.f;
-        for (int gg = 0; gg < G; ++gg) s += part[(gg * GATE_TB + t) * E + ee];
-        zs[t * PGMOE_MAX_EXPERTS + ee] = s + (bias ? bias[ee] : 0.f);
-    }
-    __syncthreads();
-
-    // softmax + top-k: one wavefront per token; lane holds experts lane, lane+64, lane+128, lane+192
     const int lane = tid & 63, wave = tid >> 6;
     for (int t = wave; t < nt; t += GATE_THREADS / 64) {
         float v[4];
@@ -140,16 +98,157 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_kernel(
     }
 }
 
+template <typename XT>
+__global__ __launch_bounds__(GATE_THREADS) void gate_topk_kernel(
+    const XT *__restrict__ x, const XT *__restrict__ w, const float *__restrict__ bias, int T, int d, int E, int k,
+    int32_t *__restrict__ idx_out, float *__restrict__ prob_out, float *__restrict__ probs_out, uint32_t *flags) {
+    __shared__ float xs[GATE_TB * GATE_DC];
+    __shared__ float part[GATE_THREADS * GATE_TB];  // [G][TB][E], G*E <= 256
+    __shared__ float zs[GATE_TB * PGMOE_MAX_EXPERTS];
+
+    const int tid = threadIdx.x;
+    const int t0 = blockIdx.x * GATE_TB;
+    const int nt = min(GATE_TB, T - t0);
+    const int G = GATE_THREADS / E;
+    const int g = tid / E, e = tid - g * E;
+    const bool active = g < G;
+
+    float acc[GATE_TB];
+#pragma unroll
+    for (int t = 0; t < GATE_TB; ++t) acc[t] = 0.f;
+
+    for (int c0 = 0; c0 < d; c0 += GATE_DC) {
+        const int dc = min(GATE_DC, d - c0);
+        __syncthreads();
+        for (int i = tid; i < GATE_TB * dc; i += GATE_THREADS) {
+            const int t = i / dc, c = i - t * dc;
+            xs[t * GATE_DC + c] = t < nt ? to_float(x[(size_t)(t0 + t) * d + c0 + c]) : 0.f;
+        }
+        __syncthreads();
+        if (active) {
+            for (int i = g; i < dc; i += G) {
+                const float wv = to_float(w[(size_t)(c0 + i) * E + e]);
+#pragma unroll
+                for (int t = 0; t < GATE_TB; ++t) acc[t] = fmaf(xs[t * GATE_DC + i], wv, acc[t]);
+            }
+        }
+    }
+    if (active) {
+#pragma unroll
+        for (int t = 0; t < GATE_TB; ++t) part[(g * GATE_TB + t) * E + e] = acc[t];
+    }
+    __syncthreads();
+    for (int o = tid; o < GATE_TB * E; o += GATE_THREADS) {
+        const int t = o / E, ee = o - t * E;
+        float s = 0.f;
+        for (int gg = 0; gg < G; ++gg) s += part[(gg * GATE_TB + t) * E + ee];
+        zs[t * PGMOE_MAX_EXPERTS + ee] = s + (bias ? bias[ee] : 0.f);
+    }
+    __syncthreads();
+
+    softmax_topk(zs, t0, nt, E, k, idx_out, prob_out, probs_out, flags);
+}
+
+// Fast path for E in {8, 16, 32, 64, 128, 256}: thread (rg, cv) owns the 8 experts 8*cv..8*cv+7
+// (one 16-byte load of a W row for bf16, two for f32) and every RG-th feature row, so the 256
+// threads sweep W in fully contiguous 4 KiB strides.  The RG partial sums per expert are folded
+// with a fixed butterfly inside the wavefront and then across the 4 wavefronts in order.
+template <typename XT, int TB>
+__global__ __launch_bounds__(GATE_THREADS) void gate_topk_vec_kernel(
+    const XT *__restrict__ x, const XT *__restrict__ w, const float *__restrict__ bias, int T, int d, int E, int k,
+    int32_t *__restrict__ idx_out, float *__restrict__ prob_out, float *__restrict__ probs_out, uint32_t *flags) {
+    __shared__ float xs[TB * GATE_DC];
+    __shared__ float part[4 * TB * PGMOE_MAX_EXPERTS];
+    __shared__ float zs[TB * PGMOE_MAX_EXPERTS];
+    typedef XT vec8 __attribute__((ext_vector_type(8)));
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t0 = blockIdx.x * TB;
+    const int nt = min(TB, T - t0);
+    const int CV = E >> 3;            // 8-expert column vectors per row (power of two, <= 32)
+    const int RG = GATE_THREADS / CV; // row groups
+    const int cv = tid & (CV - 1), rg = tid / CV;
+
+    float acc[TB][8];
+#pragma unroll
+    for (int t = 0; t < TB; ++t)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[t][j] = 0.f;
+
+    for (int c0 = 0; c0 < d; c0 += GATE_DC) {
+        const int dc = min(GATE_DC, d - c0);
+        __syncthreads();
+        for (int i = tid; i < TB * dc; i += GATE_THREADS) {
+            const int t = i / dc, c = i - t * dc;
+            xs[t * GATE_DC + c] = t < nt ? to_float(x[(size_t)(t0 + t) * d + c0 + c]) : 0.f;
+        }
+        __syncthreads();
+        const vec8 *wv = reinterpret_cast<const vec8 *>(w + (size_t)c0 * E) + cv;
+#pragma unroll 4
+        for (int i = rg; i < dc; i += RG) {
+            const vec8 v = wv[(size_t)i * CV];
+            float xr[TB];
+#pragma unroll
+            for (int t = 0; t < TB; ++t) xr[t] = xs[t * GATE_DC + i];
+#pragma unroll
+            for (int t = 0; t < TB; ++t)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[t][j] = fmaf(xr[t], to_float(v[j]), acc[t][j]);
+        }
+    }
+    // fold the row groups that live in this wavefront (lanes with equal cv are CV apart)
+    for (int off = 32; off >= CV; off >>= 1) {
+#pragma unroll
+        for (int t = 0; t < TB; ++t)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[t][j] += __shfl_xor(acc[t][j], off);
+    }
+    if (lane < CV) {
+#pragma unroll
+        for (int t = 0; t < TB; ++t)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) part[(wave * TB + t) * PGMOE_MAX_EXPERTS + 8 * lane + j] = acc[t][j];
+    }
+    __syncthreads();
+    for (int o = tid; o < TB * E; o += GATE_THREADS) {
+        const int t = o / E, e = o - t * E;
+        float sum = part[t * PGMOE_MAX_EXPERTS + e];
+#pragma unroll
+        for (int wv2 = 1; wv2 < 4; ++wv2) sum += part[(wv2 * TB + t) * PGMOE_MAX_EXPERTS + e];
+        zs[t * PGMOE_MAX_EXPERTS + e] = sum + (bias ? bias[e] : 0.f);
+    }
+    __syncthreads();
+    softmax_topk(zs, t0, nt, E, k, idx_out, prob_out, probs_out, flags);
+}
+
+template <typename XT>
+static void launch_gate_t(const pgmoe_config &c, const XT *x, const XT *w, const float *bias, int T, int32_t *idx,
+                          float *prob, float *probs, uint32_t *flags, hipStream_t s) {
+    const int E = c.n_experts;
+    const bool vec = E >= 8 && E <= PGMOE_MAX_EXPERTS && (E & (E - 1)) == 0;
+    if (!vec) {
+        hipLaunchKernelGGL(gate_topk_kernel<XT>, dim3((T + GATE_TB - 1) / GATE_TB), dim3(GATE_THREADS), 0, s, x, w, bias, T,
+                           c.d_model, E, c.top_k, idx, prob, probs, flags);
+        return;
+    }
+    // tokens per workgroup: as few as keeps about 64 workgroups busy (each re-reads W from L2)
+#define PG_GATE(TB_)                                                                                                  \
+    hipLaunchKernelGGL((gate_topk_vec_kernel<XT, TB_>), dim3((T + TB_ - 1) / TB_), dim3(GATE_THREADS), 0, s, x, w, bias, T, \
+                       c.d_model, E, c.top_k, idx, prob, probs, flags)
+    if (T <= 64) PG_GATE(1);
+    else if (T <= 128) PG_GATE(2);
+    else if (T <= 256) PG_GATE(4);
+    else PG_GATE(8);
+#undef PG_GATE
+}
+
 int launch_gate(pgmoe_ctx *ctx, const void *x, const void *w, const float *bias, int T, int32_t *idx,
                 float *prob, float *probs, hipStream_t s) {
     const pgmoe_config &c = ctx->cfg;
-    const int grid = (T + GATE_TB - 1) / GATE_TB;
     if (c.dtype == PGMOE_F32)
-        hipLaunchKernelGGL(gate_topk_kernel<float>, dim3(grid), dim3(GATE_THREADS), 0, s, (const float *)x,
-                           (const float *)w, bias, T, c.d_model, c.n_experts, c.top_k, idx, prob, probs, ctx->dev_flags);
+        launch_gate_t<float>(c, (const float *)x, (const float *)w, bias, T, idx, prob, probs, ctx->dev_flags, s);
     else
-        hipLaunchKernelGGL(gate_topk_kernel<__bf16>, dim3(grid), dim3(GATE_THREADS), 0, s, (const __bf16 *)x,
-                           (const __bf16 *)w, bias, T, c.d_model, c.n_experts, c.top_k, idx, prob, probs, ctx->dev_flags);
+        launch_gate_t<__bf16>(c, (const __bf16 *)x, (const __bf16 *)w, bias, T, idx, prob, probs, ctx->dev_flags, s);
     PG_HIP(ctx, hipGetLastError());
     return PGMOE_OK;
 }
