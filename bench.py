@@ -1,20 +1,24 @@
 #!/usr/bin/env python3
 """Benchmark of the pre-gated MoE hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--also cfg3,cfg4] [--all]
 
 A "step" is one pass of the whole hot path over one batch: conventional gate of block 0,
 pre-gates, migration of the pre-gated experts from pinned host memory, token grouping,
 expert FFNs and weighted combine, for all L blocks of the stack.  Inputs (hidden states of
 every step, gate weights) are resident in HBM before the timed region; the expert store is in
 pinned host memory (offloaded workloads) or in HBM (resident workloads), as the workload says.
-Prints ONE JSON line.
+
+Prints ONE JSON line.  The headline numbers are those of --workload (default: the
+Switch-Base-8 decode stack); --also adds abbreviated results of other workloads under
+"other_workloads" (same measurement, fewer steps).
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -32,8 +36,6 @@ def log(msg):
 
 def cpu_baseline(w, steps_sample):
     """Time the CPU oracle (as it stands) on a bounded sample of the same workload."""
-    import numpy as np
-
     import workloads as W
     from oracle import reference as R
 
@@ -60,41 +62,63 @@ def cpu_baseline(w, steps_sample):
             "ms_per_token_per_layer": 1e3 * dt / (w.tokens * steps_sample * w.n_blocks)}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="cfg2")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-steps", type=int, default=None)
-    ap.add_argument("--host-threads", type=int, default=16)
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
-        sys.exit(2)
+def measured_peaks():
+    """Plain-copy rates of this machine, for context next to the nominal peaks (torch copies only)."""
+    import torch
+    n = 1 << 30
+    a = torch.empty(n, dtype=torch.uint8, device="cuda")
+    b = torch.empty(n, dtype=torch.uint8, device="cuda")
+    h = torch.empty(256 << 20, dtype=torch.uint8, pin_memory=True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    b.copy_(a)
+    a[: h.numel()].copy_(h, non_blocking=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(5):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    d2d = 2.0 * n * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    e0.record()
+    for _ in range(4):
+        a[: h.numel()].copy_(h, non_blocking=True)
+    e1.record()
+    torch.cuda.synchronize()
+    h2d = h.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    return {"hbm_copy_read_plus_write_GBps": d2d, "h2d_pinned_256MiB_GBps": h2d}
 
+
+def pmc_traffic(workload_name):
+    """HBM bytes per FFN launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "ffn_fused_hbm_traffic.md")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch\[%s\]\s*=\s*([0-9.eE+]+)" % re.escape(workload_name),
+                      open(path).read(), flags=re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps):
     import numpy as np
     import torch
 
     import workloads as W
     from paper_2308_12066_amd import harness as H
 
-    w = W.CONFIGS[args.workload]
-    K = args.steps if args.steps is not None else w.steps
-    Wm = args.warmup if args.warmup is not None else max(3, min(16, K // 8))
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    w = W.CONFIGS[name]
+    K = K if K is not None else w.steps
+    Wm = Wm if Wm is not None else max(2, min(16, K // 8))
     L, T, k, E = w.n_blocks, w.tokens, w.top_k, w.n_experts
 
     t0 = time.perf_counter()
     cfg = H.config_for(w)
-    store = H.ExpertStore(w, cfg, threads=args.host_threads)
+    store = H.ExpertStore(w, cfg, threads=host_threads)
     stack = H.Stack(w, store)
     # Every timed step gets its own hidden-state block (slice 0 pre-filled with that step's
     # input) and its own routing-index slice, so the timed loop holds library calls only.
     n_in = min(K, max(1, (1 << 30) // ((L + 1) * T * w.d_model * w.elem_bytes)))   # distinct inputs kept in HBM
-    tdt = stack.x_states.dtype
-    x_all = torch.zeros((n_in, L + 1, T, w.d_model), dtype=tdt, device="cuda")
+    x_all = torch.zeros((n_in, L + 1, T, w.d_model), dtype=stack.x_states.dtype, device="cuda")
     for s in range(n_in):
         x_all[s, 0].copy_(H.to_device(W.step_input(w, s % max(w.steps, 1)), w.dtype))
     idx_log = torch.zeros((K, L, T, k), dtype=torch.int32, device="cuda")
@@ -104,25 +128,25 @@ def main():
     torch.cuda.synchronize()
     log(f"[bench] {w.name}: store {store.host.numel() / 2**30:.2f} GiB built in {time.perf_counter() - t0:.1f} s")
 
-    def run(first, count, log_idx):
-        for s in range(first, first + count):
+    def run(count):
+        for s in range(count):
             stack.ctx.stack_step(step_bufs[s % K], T, stack.compute, stack.copy)
 
-    run(0, Wm, False)
+    run(Wm)
     torch.cuda.synchronize()
     # pass 1: the K timed steps, nothing but the hot path on the streams -> `value`
     t0 = time.perf_counter()
-    run(0, K, True)
+    run(K)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     # pass 2: the same K steps again with an event pair around every expert-FFN kernel launch
     # (each pair costs several microseconds on the stream, which is why pass 1 runs without)
     stack.ctx.ffn_timing_begin(K * L)
     t1 = time.perf_counter()
-    run(0, K, True)
+    run(K)
     torch.cuda.synchronize()
     dt_events = time.perf_counter() - t1
-    n_timed, ffn_ms = stack.ctx.ffn_timing_end()
+    n_timed, ffn_ms, overhead_us = stack.ctx.ffn_timing_end()
     assert stack.ctx.device_flags() == 0
 
     # algorithmic bytes of the FFN launches: weights of the distinct experts each launch touches
@@ -131,8 +155,10 @@ def main():
     uniq = np.array([[len(np.unique(idx_host[s, b])) for b in range(L)] for s in range(K)])
     act_bytes = 2 * T * k * w.d_model * w.elem_bytes
     ffn_bytes = float(uniq.sum()) * w.expert_bytes + float(K * L) * act_bytes
-    ffn_avg_us = 1e3 * ffn_ms / max(n_timed, 1)
-    ffn_gbps = ffn_bytes / max(n_timed, 1) / (ffn_avg_us * 1e-6) / 1e9 if n_timed else 0.0
+    raw_us = 1e3 * ffn_ms / max(n_timed, 1)
+    ffn_avg_us = max(raw_us - overhead_us, 1e-3)
+    per_launch = ffn_bytes / max(n_timed, 1)
+    ffn_gbps = per_launch / (ffn_avg_us * 1e-6) / 1e9 if n_timed else 0.0
     h2d_bytes = float(uniq.sum()) * w.expert_bytes if w.offloaded else 0.0
 
     out = {
@@ -155,19 +181,92 @@ def main():
         "ms_per_token_per_layer": 1e3 * dt / (T * K * L),
         "block_latency_us": 1e6 * dt / (K * L),
         "roofline": {"bound": "hbm", "achieved": ffn_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": ffn_gbps / HBM_PEAK_GBPS, "traffic": None,
-                     "kernel": "ffn_fused_kernel" if w.dtype == "bf16" else "ffn_f32_*", "launches": n_timed,
-                     "avg_launch_us": ffn_avg_us, "algorithmic_bytes_per_launch": ffn_bytes / max(n_timed, 1),
+                     "frac": ffn_gbps / HBM_PEAK_GBPS, "traffic": pmc_traffic(w.name),
+                     "kernel": "ffn_fused_kernel" if w.dtype == "bf16" else "ffn_f32_hidden_kernel+ffn_f32_out_kernel",
+                     "launches": n_timed, "avg_launch_us": ffn_avg_us, "event_pair_us": raw_us,
+                     "event_overhead_us": overhead_us, "algorithmic_bytes_per_launch": per_launch,
                      "ms_per_step_with_events": 1e3 * dt_events / K},
         "host_link": {"bytes_per_step": h2d_bytes / K, "achieved_GBps": h2d_bytes / dt / 1e9,
                       "peak_GBps": LINK_PEAK_GBPS, "frac": h2d_bytes / dt / 1e9 / LINK_PEAK_GBPS,
                       "mean_unique_experts_per_block": float(uniq.mean())},
     }
-    if not args.no_cpu_baseline:
-        sample = args.cpu_sample_steps or max(1, min(K, int(round(600.0 / (T * L * k)))))
-        log(f"[bench] timing the CPU oracle on {sample} steps")
+
+    if w.offloaded and trace_steps > 0:
+        # pass 3: instrumented steps for the overlap figures (per-block events on both streams)
+        stack.ctx.trace(True)
+        busy = busy0 = stall = stall0 = comp = fsum = 0.0
+        for s in range(trace_steps):
+            stack.ctx.stack_step(step_bufs[s % K], T, stack.compute, stack.copy)
+            torch.cuda.synchronize()
+            tr = [stack.ctx.block_trace(b) for b in range(L)]
+            # time with at least one migration in flight (the pull kernels of consecutive blocks
+            # may share the link, so their durations must not simply be added)
+            iv = sorted((t.fetch_start_ms, t.fetch_end_ms) for t in tr)
+            end = -1e30
+            for a, b in iv:
+                busy += max(0.0, b - max(a, end))
+                end = max(end, b)
+            busy0 += tr[0].fetch_ms
+            stall += sum(t.stall_ms for t in tr)
+            stall0 += tr[0].stall_ms
+            comp += sum(t.compute_ms for t in tr)
+            fsum += sum(t.fetch_ms for t in tr)
+        stack.ctx.trace(False)
+        n = float(trace_steps)
+        out["overlap"] = {
+            "steps": trace_steps,
+            "link_busy_ms_per_step": busy / n, "stall_ms_per_step": stall / n, "compute_ms_per_step": comp / n,
+            "sum_of_fetch_durations_ms_per_step": fsum / n,
+            "hidden_frac": 1.0 - stall / busy,
+            "hidden_frac_without_block0": 1.0 - (stall - stall0) / max(busy - busy0, 1e-9),
+            "hidden_frac_upper_bound": min(1.0, comp / busy),
+            "overlap_efficiency": (busy - stall) / max(min(comp, busy), 1e-9),
+            "note": "hidden = share of the time with a migration in flight during which the compute stream was not "
+                    "waiting for experts; compute = the MoE blocks only (no attention or other non-MoE layers exist "
+                    "here to hide behind); block 0's fetch is exposed by construction",
+        }
+    if with_cpu:
+        sample = cpu_steps or max(1, min(K, int(round(600.0 / (T * L * k)))))
+        log(f"[bench] {w.name}: timing the CPU oracle on {sample} steps")
         out["cpu_baseline"] = cpu_baseline(w, sample)
     stack.close()
+    del stack, store, x_all, step_bufs
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--also", default="cfg3,cfg4", help="comma list of further workloads to summarise ('' for none)")
+    ap.add_argument("--all", action="store_true", help="also run the offloaded Switch-Base-128 and both Switch-Large-128 runs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-steps", type=int, default=None)
+    ap.add_argument("--trace-steps", type=int, default=8)
+    ap.add_argument("--host-threads", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    out = run_workload(args.workload, args.steps, args.warmup, args.host_threads, not args.no_cpu_baseline,
+                       args.cpu_sample_steps, args.trace_steps)
+    out["measured_peaks"] = measured_peaks()
+    others = [n for n in args.also.split(",") if n and n != args.workload]
+    if args.all:
+        others += [n for n in ("cfg4_offloaded", "cfg5", "cfg5_top2") if n not in others]
+    short = {"cfg1": 8, "cfg3": 24, "cfg4": 4, "cfg4_offloaded": 2, "cfg5": 6, "cfg5_top2": 6, "base8_prefill": 4}
+    keep = ("value", "unit", "steps", "ms_per_step", "ms_per_token_per_layer", "block_latency_us", "config", "roofline",
+            "host_link", "overlap")
+    out["other_workloads"] = {}
+    for n in others:
+        r = run_workload(n, short.get(n, 8), 2, args.host_threads, False, None, min(args.trace_steps, 2))
+        out["other_workloads"][n] = {k: r[k] for k in keep if k in r}
     print(json.dumps(out), flush=True)
 
 

@@ -237,11 +237,35 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
  * (the fused bf16 kernel, or the two f32 kernels; not the small partial-sum reduction) with a
  * pair of HIP events on the stream it is launched on, for up to max_launches launches (the
  * events are created here, not in the hot path; later launches are not timed).
- * pgmoe_ffn_timing_end() waits for the recorded events, returns the number of timed launches
- * and the sum of their event-to-event times in milliseconds, and switches timing off.
- * n_out, total_ms_out host. */
+ * pgmoe_ffn_timing_begin() also measures what an event pair itself adds: the median
+ * event-to-event time around an empty kernel minus the period of back-to-back empty kernels
+ * (the part of that time the empty kernel itself accounts for).
+ * pgmoe_ffn_timing_end() waits for the recorded events, returns the number of timed launches,
+ * the sum of their event-to-event times in milliseconds and that per-pair overhead (to be
+ * subtracted per launch), and switches timing off.
+ * n_out, total_ms_out host; pair_overhead_ms_out host | NULL. */
 int pgmoe_ffn_timing_begin(pgmoe_ctx *ctx, int max_launches);
-int pgmoe_ffn_timing_end(pgmoe_ctx *ctx, int *n_out, float *total_ms_out);
+int pgmoe_ffn_timing_end(pgmoe_ctx *ctx, int *n_out, float *total_ms_out, float *pair_overhead_ms_out);
+
+/* ---- observability: per-block timeline of pgmoe_stack_step -------------------------------
+ * With tracing on, every stack step records timing events per block: on the copy stream
+ * around the migration, on the compute stream at the start of the block, just before and just
+ * after the point where the FFN waits for its experts, and at the end of the block.  The event
+ * records cost several microseconds each, so tracing is for instrumented passes only.
+ * pgmoe_get_block_trace() waits for the block's events of the LAST step and fills:
+ *   fetch_ms   duration of the block's migration (copy stream);
+ *   stall_ms   time the compute stream spent waiting for it (0 if the experts were there);
+ *   compute_ms duration of the block on the compute stream (pre-gate, grouping, FFN, combine)
+ *              minus stall_ms;
+ *   fetch_start_ms, fetch_end_ms, block_start_ms, block_end_ms: the same events as offsets
+ *              from the start of block 0 on the compute stream. */
+typedef struct {
+    float fetch_ms, stall_ms, compute_ms;
+    float fetch_start_ms, fetch_end_ms, block_start_ms, block_end_ms;
+    float reserved;
+} pgmoe_block_trace;
+int pgmoe_trace(pgmoe_ctx *ctx, int enable);
+int pgmoe_get_block_trace(pgmoe_ctx *ctx, int block, pgmoe_block_trace *out /* host */);
 
 /* Sticky device-side condition bits since the last call of this function (synchronises the
  * device): bit 0 = a NaN logit was seen by a gate, bit 1 = an expert index outside [0,E)

@@ -24,7 +24,7 @@ EXPORTS = [
     "pgmoe_pack_expert", "pgmoe_unpack_expert", "pgmoe_pregate_topk", "pgmoe_register_host_experts",
     "pgmoe_register_resident_experts", "pgmoe_fetch_experts", "pgmoe_get_fetch_stats", "pgmoe_unique_experts",
     "pgmoe_permute", "pgmoe_expert_ffn", "pgmoe_combine", "pgmoe_stack_step", "pgmoe_device_flags",
-    "pgmoe_ffn_timing_begin", "pgmoe_ffn_timing_end", "pgmoe_slot_address", "pgmoe_fetch_timing",
+    "pgmoe_ffn_timing_begin", "pgmoe_ffn_timing_end", "pgmoe_slot_address", "pgmoe_fetch_timing", "pgmoe_trace", "pgmoe_get_block_trace",
 ]
 
 
@@ -37,6 +37,11 @@ class Config(Structure):
 class FetchStats(Structure):
     _fields_ = [("n_unique", c_int32), ("n_copied", c_int32), ("bytes_copied", c_int64),
                 ("resident_slots", c_int32), ("reserved", c_int32), ("fetch_ms", c_float), ("wait_ms", c_float)]
+
+
+class BlockTrace(Structure):
+    _fields_ = [("fetch_ms", c_float), ("stall_ms", c_float), ("compute_ms", c_float), ("fetch_start_ms", c_float),
+                ("fetch_end_ms", c_float), ("block_start_ms", c_float), ("block_end_ms", c_float), ("reserved", c_float)]
 
 
 class StepBuffers(Structure):
@@ -79,8 +84,10 @@ def _load():
     L.pgmoe_device_flags.argtypes = [vp, POINTER(c_uint32)]
     L.pgmoe_ffn_timing_begin.argtypes = [vp, i]
     L.pgmoe_fetch_timing.argtypes = [vp, i]
+    L.pgmoe_trace.argtypes = [vp, i]
+    L.pgmoe_get_block_trace.argtypes = [vp, i, POINTER(BlockTrace)]
     L.pgmoe_slot_address.argtypes = [vp, i, i, POINTER(vp)]
-    L.pgmoe_ffn_timing_end.argtypes = [vp, POINTER(c_int), POINTER(c_float)]
+    L.pgmoe_ffn_timing_end.argtypes = [vp, POINTER(c_int), POINTER(c_float), POINTER(c_float)]
     for name in EXPORTS:
         if name not in ("pgmoe_last_error", "pgmoe_expert_bytes", "pgmoe_workspace_bytes"):
             getattr(L, name).restype = c_int
@@ -234,10 +241,10 @@ class Context:
         self._check(lib.pgmoe_ffn_timing_begin(self._h, max_launches))
 
     def ffn_timing_end(self):
-        """-> (number of timed launches, sum of their durations in ms)."""
-        n, ms = c_int(0), c_float(0.0)
-        self._check(lib.pgmoe_ffn_timing_end(self._h, byref(n), byref(ms)))
-        return n.value, ms.value
+        """-> (timed launches, sum of their event-to-event times in ms, per-pair event overhead in us)."""
+        n, ms, oh = c_int(0), c_float(0.0), c_float(0.0)
+        self._check(lib.pgmoe_ffn_timing_end(self._h, byref(n), byref(ms), byref(oh)))
+        return n.value, ms.value, oh.value * 1e3
 
     def slot_address(self, block: int, slot: int) -> int:
         p = c_void_p()
@@ -246,3 +253,11 @@ class Context:
 
     def fetch_timing(self, enable: bool):
         self._check(lib.pgmoe_fetch_timing(self._h, 1 if enable else 0))
+
+    def trace(self, enable: bool):
+        self._check(lib.pgmoe_trace(self._h, 1 if enable else 0))
+
+    def block_trace(self, block: int) -> BlockTrace:
+        t = BlockTrace()
+        self._check(lib.pgmoe_get_block_trace(self._h, block, byref(t)))
+        return t

@@ -86,6 +86,37 @@ static void tile_copy(uint16_t *tiled, uint16_t *plain, int K, int N, bool nt_ma
 
 using namespace pgmoe;
 
+__global__ void noop_kernel() {}
+
+// Median event-to-event time around an empty kernel minus the period of back-to-back empty
+// kernels: the share of an event pair's reading that is not kernel time.
+static int measure_pair_overhead(pgmoe_ctx *ctx, float *out_ms) {
+    constexpr int N = 33;
+    hipStream_t s = ctx->copy2;  // any idle stream of the context
+    hipEvent_t ev[2 * N];
+    for (auto &e : ev) PG_HIP(ctx, hipEventCreate(&e));
+    for (int i = 0; i < 8; ++i) hipLaunchKernelGGL(noop_kernel, dim3(1), dim3(64), 0, s);
+    for (int i = 0; i < N; ++i) {
+        PG_HIP(ctx, hipEventRecord(ev[2 * i], s));
+        hipLaunchKernelGGL(noop_kernel, dim3(1), dim3(64), 0, s);
+        PG_HIP(ctx, hipEventRecord(ev[2 * i + 1], s));
+    }
+    PG_HIP(ctx, hipStreamSynchronize(s));
+    float pair[N];
+    for (int i = 0; i < N; ++i) PG_HIP(ctx, hipEventElapsedTime(&pair[i], ev[2 * i], ev[2 * i + 1]));
+    std::sort(pair, pair + N);
+    PG_HIP(ctx, hipEventRecord(ev[0], s));
+    for (int i = 0; i < 64; ++i) hipLaunchKernelGGL(noop_kernel, dim3(1), dim3(64), 0, s);
+    PG_HIP(ctx, hipEventRecord(ev[1], s));
+    PG_HIP(ctx, hipStreamSynchronize(s));
+    float run = 0.f;
+    PG_HIP(ctx, hipEventElapsedTime(&run, ev[0], ev[1]));
+    for (auto &e : ev) (void)hipEventDestroy(e);
+    const float oh = pair[N / 2] - run / 64.f;
+    *out_ms = oh > 0.f ? oh : 0.f;
+    return PGMOE_OK;
+}
+
 static void free_timing(pgmoe_ctx *c) {
     for (int i = 0; i < c->tim_cap; ++i) {
         if (c->tim_begin && c->tim_begin[i]) (void)hipEventDestroy(c->tim_begin[i]);
@@ -160,12 +191,12 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
             H(hipEventCreateWithFlags(&c->ffn_done[g], hipEventDisableTiming | hipEventReleaseToDevice), "hipEventCreate");
         }
         if (rc == PGMOE_OK) {
-            c->fetch_begin = new (std::nothrow) hipEvent_t[cfg->n_blocks]();
-            c->fetch_end = new (std::nothrow) hipEvent_t[cfg->n_blocks]();
-            for (int b = 0; b < cfg->n_blocks && rc == PGMOE_OK; ++b) {
-                H(hipEventCreate(&c->fetch_begin[b]), "hipEventCreate");
-                H(hipEventCreate(&c->fetch_end[b]), "hipEventCreate");
+            hipEvent_t **arrays[] = {&c->fetch_begin, &c->fetch_end, &c->ev_c0, &c->ev_ready, &c->ev_waited, &c->ev_c1};
+            for (hipEvent_t **a : arrays) {
+                *a = new (std::nothrow) hipEvent_t[cfg->n_blocks]();
+                for (int b = 0; b < cfg->n_blocks && rc == PGMOE_OK; ++b) H(hipEventCreate(&(*a)[b]), "hipEventCreate");
             }
+            c->traced = new (std::nothrow) bool[cfg->n_blocks]();
         }
         if (rc != PGMOE_OK) {
             pgmoe_destroy(c);
@@ -189,12 +220,13 @@ int pgmoe_destroy(pgmoe_ctx *c) {
             if (c->fetch_done[g]) (void)hipEventDestroy(c->fetch_done[g]);
             if (c->ffn_done[g]) (void)hipEventDestroy(c->ffn_done[g]);
         }
-        for (int b = 0; b < c->cfg.n_blocks; ++b) {
-            if (c->fetch_begin && c->fetch_begin[b]) (void)hipEventDestroy(c->fetch_begin[b]);
-            if (c->fetch_end && c->fetch_end[b]) (void)hipEventDestroy(c->fetch_end[b]);
+        hipEvent_t *arrays[] = {c->fetch_begin, c->fetch_end, c->ev_c0, c->ev_ready, c->ev_waited, c->ev_c1};
+        for (hipEvent_t *a : arrays) {
+            for (int b = 0; a && b < c->cfg.n_blocks; ++b)
+                if (a[b]) (void)hipEventDestroy(a[b]);
+            delete[] a;
         }
-        delete[] c->fetch_begin;
-        delete[] c->fetch_end;
+        delete[] c->traced;
         free_timing(c);
     }
     delete[] c->stats;
@@ -339,12 +371,14 @@ int pgmoe_ffn_timing_begin(pgmoe_ctx *ctx, int max_launches) {
             PG_HIP(ctx, hipEventCreate(&ctx->tim_end[i]));
         }
     }
+    int rc = measure_pair_overhead(ctx, &ctx->tim_overhead_ms);
+    if (rc) return rc;
     ctx->tim_n = 0;
     ctx->tim_on = true;
     return PGMOE_OK;
 }
 
-int pgmoe_ffn_timing_end(pgmoe_ctx *ctx, int *n_out, float *total_ms_out) {
+int pgmoe_ffn_timing_end(pgmoe_ctx *ctx, int *n_out, float *total_ms_out, float *pair_overhead_ms_out) {
     const char *fn = "pgmoe_ffn_timing_end";
     if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
     if (!n_out || !total_ms_out) return fail(ctx, PGMOE_EINVAL, "%s: NULL output pointer", fn);
@@ -359,6 +393,7 @@ int pgmoe_ffn_timing_end(pgmoe_ctx *ctx, int *n_out, float *total_ms_out) {
     }
     *n_out = ctx->tim_n;
     *total_ms_out = (float)total;
+    if (pair_overhead_ms_out) *pair_overhead_ms_out = ctx->tim_overhead_ms;
     return PGMOE_OK;
 }
 

@@ -227,6 +227,40 @@ int pgmoe_fetch_timing(pgmoe_ctx *ctx, int enable) {
     return PGMOE_OK;
 }
 
+int pgmoe_trace(pgmoe_ctx *ctx, int enable) {
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "pgmoe_trace: ctx is NULL");
+    ctx->trace = enable != 0;
+    ctx->fetch_timing = enable != 0;
+    for (int b = 0; ctx->traced && b < ctx->cfg.n_blocks; ++b) ctx->traced[b] = false;
+    return PGMOE_OK;
+}
+
+int pgmoe_get_block_trace(pgmoe_ctx *ctx, int block, pgmoe_block_trace *out) {
+    const char *fn = "pgmoe_get_block_trace";
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
+    int rc = check_block(ctx, fn, block);
+    if (rc) return rc;
+    if (!out) return fail(ctx, PGMOE_EINVAL, "%s: out is NULL", fn);
+    if (ctx->host_only) return fail(ctx, PGMOE_ENODEVICE, "%s: context is host-only", fn);
+    if (!ctx->traced || !ctx->traced[block])
+        return fail(ctx, PGMOE_ESTATE, "%s: block %d has no trace (tracing on, host store, a stack step run?)", fn, block);
+    PG_HIP(ctx, hipEventSynchronize(ctx->ev_c1[block]));
+    PG_HIP(ctx, hipEventSynchronize(ctx->fetch_end[block]));
+    auto el = [&](hipEvent_t a, hipEvent_t b, float *ms) { return hipEventElapsedTime(ms, a, b); };
+    float stall = 0.f, total = 0.f;
+    memset(out, 0, sizeof *out);
+    PG_HIP(ctx, el(ctx->fetch_begin[block], ctx->fetch_end[block], &out->fetch_ms));
+    PG_HIP(ctx, el(ctx->ev_ready[block], ctx->ev_waited[block], &stall));
+    PG_HIP(ctx, el(ctx->ev_c0[block], ctx->ev_c1[block], &total));
+    PG_HIP(ctx, el(ctx->ev_c0[0], ctx->fetch_begin[block], &out->fetch_start_ms));
+    PG_HIP(ctx, el(ctx->ev_c0[0], ctx->fetch_end[block], &out->fetch_end_ms));
+    PG_HIP(ctx, el(ctx->ev_c0[0], ctx->ev_c0[block], &out->block_start_ms));
+    PG_HIP(ctx, el(ctx->ev_c0[0], ctx->ev_c1[block], &out->block_end_ms));
+    out->stall_ms = stall > 0.f ? stall : 0.f;
+    out->compute_ms = total - out->stall_ms;
+    return PGMOE_OK;
+}
+
 int pgmoe_slot_address(pgmoe_ctx *ctx, int block, int slot, void **dev_out) {
     const char *fn = "pgmoe_slot_address";
     if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
@@ -259,7 +293,9 @@ int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_
     const int gen = block & 1;
     if (ctx->fetched_block[gen] != block)
         return fail(ctx, PGMOE_ESTATE, "%s: block %d was not fetched (generation holds block %d)", fn, block, ctx->fetched_block[gen]);
+    if (ctx->trace) PG_HIP(ctx, hipEventRecord(ctx->ev_ready[block], s));
     if (ctx->fetch_stream[gen] != s) PG_HIP(ctx, hipStreamWaitEvent(s, ctx->fetch_done[gen], 0));
+    if (ctx->trace) PG_HIP(ctx, hipEventRecord(ctx->ev_waited[block], s));
     rc = launch_ffn(ctx, ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes, ctx->expert_bytes, true, ctx->slots,
                     x_perm, expert_offsets, n_rows, y_perm, workspace, s);
     if (rc) return rc;
@@ -292,6 +328,7 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     auto bias_at = [&](int g) -> const float * { return io->gate_b ? io->gate_b[g] : nullptr; };
     int rc;
 
+    if (ctx->trace) PG_HIP(ctx, hipEventRecord(ctx->ev_c0[0], (hipStream_t)compute_stream));
     // Block 0: its own (conventional) gate and, on the same input, pre-gate 0 for block 1.  Both
     // routings are known before anything can execute, so block 0's exposed fetch and block 1's
     // fetch are queued back to back on the copy stream: the link never idles between them.
@@ -309,6 +346,7 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     }
 
     for (int i = 0; i < L; ++i) {
+        if (ctx->trace && i > 0) PG_HIP(ctx, hipEventRecord(ctx->ev_c0[i], (hipStream_t)compute_stream));
         // pre-gate of block i routes block i+1; its experts start moving before block i executes
         if (i > 0 && i + 1 < L) {
             rc = pgmoe_pregate_topk(ctx, x_at(i), io->gate_w[i + 1], bias_at(i + 1), T, idx_at(i + 1), prob_at(i + 1), nullptr,
@@ -326,6 +364,10 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
         void *y = io->y_blocks ? (char *)io->y_blocks + (size_t)i * xbytes : nullptr;
         rc = pgmoe_combine(ctx, io->y_perm, row_of, prob_at(i), T, y, x_at(i), x_at(i + 1), compute_stream);
         if (rc) return rc;
+        if (ctx->trace) {
+            PG_HIP(ctx, hipEventRecord(ctx->ev_c1[i], (hipStream_t)compute_stream));
+            ctx->traced[i] = ctx->store_mode == STORE_HOST && ctx->fetch_timing;
+        }
     }
     return PGMOE_OK;
 }

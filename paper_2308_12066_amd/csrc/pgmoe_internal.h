@@ -64,12 +64,16 @@ struct pgmoe_ctx {
     hipStream_t fetch_stream[pgmoe::kGen];  // stream the generation's last fetch ran on
     hipStream_t copy2;                      // internal copy stream for odd generations
     bool fetch_timing;               // record fetch_begin / fetch_end
+    bool trace;                      // record the per-block compute-stream events below
+    hipEvent_t *ev_c0, *ev_ready, *ev_waited, *ev_c1;  // [n_blocks] each
+    bool *traced;                    // [n_blocks] events of the last step are valid
     pgmoe::BlockStats *stats;  // [n_blocks]
 
     // optional timing of the FFN kernel (pgmoe_ffn_timing_begin/end)
     hipEvent_t *tim_begin, *tim_end;
     int tim_cap, tim_n;
     bool tim_on;
+    float tim_overhead_ms;  // what one event pair adds around a kernel
 
     char err[512];
 };
