@@ -99,7 +99,7 @@ def pmc_traffic(workload_name):
         return None
 
 
-def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps):
+def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gpu_only=True):
     import numpy as np
     import torch
 
@@ -128,26 +128,29 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps):
     torch.cuda.synchronize()
     log(f"[bench] {w.name}: store {store.host.numel() / 2**30:.2f} GiB built in {time.perf_counter() - t0:.1f} s")
 
-    def run(count):
-        for s in range(count):
-            stack.ctx.stack_step(step_bufs[s % K], T, stack.compute, stack.copy)
+    def two_passes(stk, bufs):
+        """pass 1: K steps, nothing but the hot path on the streams (-> step time);
+        pass 2: the same K steps with an event pair around every expert-FFN kernel launch (each
+        pair costs several microseconds on the stream, which is why pass 1 runs without)."""
+        def run(count):
+            for s in range(count):
+                stk.ctx.stack_step(bufs[s % K], T, stk.compute, stk.copy)
+        run(Wm)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(K)
+        torch.cuda.synchronize()
+        dt_clean = time.perf_counter() - t0
+        stk.ctx.ffn_timing_begin(K * L)
+        t1 = time.perf_counter()
+        run(K)
+        torch.cuda.synchronize()
+        dt_ev = time.perf_counter() - t1
+        n_t, ms, oh = stk.ctx.ffn_timing_end()
+        assert stk.ctx.device_flags() == 0
+        return dt_clean, dt_ev, n_t, ms, oh
 
-    run(Wm)
-    torch.cuda.synchronize()
-    # pass 1: the K timed steps, nothing but the hot path on the streams -> `value`
-    t0 = time.perf_counter()
-    run(K)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    # pass 2: the same K steps again with an event pair around every expert-FFN kernel launch
-    # (each pair costs several microseconds on the stream, which is why pass 1 runs without)
-    stack.ctx.ffn_timing_begin(K * L)
-    t1 = time.perf_counter()
-    run(K)
-    torch.cuda.synchronize()
-    dt_events = time.perf_counter() - t1
-    n_timed, ffn_ms, overhead_us = stack.ctx.ffn_timing_end()
-    assert stack.ctx.device_flags() == 0
+    dt, dt_events, n_timed, ffn_ms, overhead_us = two_passes(stack, step_bufs)
 
     # algorithmic bytes of the FFN launches: weights of the distinct experts each launch touches
     # plus its activation rows in and out
@@ -225,6 +228,23 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps):
                     "waiting for experts; compute = the MoE blocks only (no attention or other non-MoE layers exist "
                     "here to hide behind); block 0's fetch is exposed by construction",
         }
+    if w.offloaded and gpu_only:
+        # The paper's GPU-only design point on the same workload: every expert resident in HBM,
+        # nothing migrates.  Also gives the FFN kernel's duration without a migration kernel
+        # running next to it.
+        w2 = w.replace(offloaded=False)
+        stack2 = H.Stack(w2, store)
+        bufs2 = [stack2.ctx.make_step_buffers(stack2.gate_w, stack2.gate_b, x_all[s % n_in], stack2.y_blocks, idx_log[s],
+                                              stack2.topk_prob, stack2.row_of, stack2.expert_offsets, stack2.x_perm,
+                                              stack2.y_perm, stack2.workspace) for s in range(K)]
+        dt2, _, n2, ms2, oh2 = two_passes(stack2, bufs2)
+        us2 = max(1e3 * ms2 / max(n2, 1) - oh2, 1e-3)
+        out["gpu_only"] = {"value": T * K / dt2, "unit": "tokens/s", "ms_per_step": 1e3 * dt2 / K,
+                           "ffn_avg_launch_us": us2, "ffn_achieved_GBps": per_launch / (us2 * 1e-6) / 1e9,
+                           "ffn_frac_of_hbm_peak": per_launch / (us2 * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                           "note": "same workload and routing with all experts resident in HBM (no migration)"}
+        stack2.close()
+        del stack2, bufs2
     if with_cpu:
         sample = cpu_steps or max(1, min(K, int(round(600.0 / (T * L * k)))))
         log(f"[bench] {w.name}: timing the CPU oracle on {sample} steps")
@@ -262,7 +282,7 @@ def main():
         others += [n for n in ("cfg4_offloaded", "cfg5", "cfg5_top2") if n not in others]
     short = {"cfg1": 8, "cfg3": 24, "cfg4": 4, "cfg4_offloaded": 2, "cfg5": 6, "cfg5_top2": 6, "base8_prefill": 4}
     keep = ("value", "unit", "steps", "ms_per_step", "ms_per_token_per_layer", "block_latency_us", "config", "roofline",
-            "host_link", "overlap")
+            "host_link", "overlap", "gpu_only")
     out["other_workloads"] = {}
     for n in others:
         r = run_workload(n, short.get(n, 8), 2, args.host_threads, False, None, min(args.trace_steps, 2))

@@ -235,31 +235,37 @@ __global__ __launch_bounds__(NW * 64) void ffn_fused_kernel(
     }
 }
 
-// y_perm[row][c] = bf16( sum_p partial[p][row][c] ).  A workgroup covers 16 float4 columns;
-// its 16 "p-lanes" each add every 16th partial (p = pl, pl+16, ...) and the 16 sub-sums are
-// added in fixed order, so the result does not depend on scheduling.
+// y_perm[row][c] = bf16( sum_p partial[p][row][c] ).  A workgroup of 256 threads covers 256/PL
+// float4 columns; its PL "p-lanes" each add every PL-th partial (p = pl, pl+PL, ...) and the PL
+// sub-sums are added in ascending order, so the result does not depend on scheduling.  PL is
+// picked from P alone (1 for P <= 2, 4 for P <= 8, else 16).
+template <int PL>
 __global__ __launch_bounds__(256) void ffn_reduce_kernel(const float *__restrict__ partial, int P, int n_rows, int d,
                                                           __bf16 *__restrict__ y_perm) {
-    __shared__ floatx4 sub[16][17];
+    constexpr int COLS = 256 / PL;
+    __shared__ floatx4 sub[PL][COLS + 1];
     const size_t total4 = (size_t)n_rows * d / 4;
-    const int col = threadIdx.x & 15, pl = threadIdx.x >> 4;
-    const size_t i = (size_t)blockIdx.x * 16 + col;
+    const int col = threadIdx.x % COLS, pl = threadIdx.x / COLS;
+    const size_t i = (size_t)blockIdx.x * COLS + col;
     floatx4 s = floatx4{0.f, 0.f, 0.f, 0.f};
     if (i < total4) {
         const floatx4 *src = reinterpret_cast<const floatx4 *>(partial) + i;
-        for (int p = pl; p < P; p += 16) s += src[(size_t)p * total4];
+        for (int p = pl; p < P; p += PL) s += src[(size_t)p * total4];
     }
-    sub[pl][col] = s;
-    __syncthreads();
-    if (pl == 0 && i < total4) {
-        floatx4 t = sub[0][col];
+    if (PL > 1) {
+        sub[pl][col] = s;
+        __syncthreads();
+        if (pl != 0) return;
+        s = sub[0][col];
 #pragma unroll
-        for (int k = 1; k < 16; ++k) t += sub[k][col];
+        for (int k = 1; k < PL; ++k) s += sub[k][col];
+    }
+    if (i < total4) {
         bf16x4 o;
-        o.x = (__bf16)t.x;
-        o.y = (__bf16)t.y;
-        o.z = (__bf16)t.z;
-        o.w = (__bf16)t.w;
+        o.x = (__bf16)s.x;
+        o.y = (__bf16)s.y;
+        o.z = (__bf16)s.z;
+        o.w = (__bf16)s.w;
         reinterpret_cast<bf16x4 *>(y_perm)[i] = o;
     }
 }
@@ -409,8 +415,15 @@ static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, si
     if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
     if (partial) {
         const size_t total4 = (size_t)n_rows * c.d_model / 4;
-        hipLaunchKernelGGL(ffn_reduce_kernel, dim3((unsigned)((total4 + 15) / 16)), dim3(256), 0, s, partial, p.n_partial,
-                           n_rows, c.d_model, (__bf16 *)y_perm);
+        if (p.n_partial <= 2)
+            hipLaunchKernelGGL(ffn_reduce_kernel<1>, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, partial,
+                               p.n_partial, n_rows, c.d_model, (__bf16 *)y_perm);
+        else if (p.n_partial <= 8)
+            hipLaunchKernelGGL(ffn_reduce_kernel<4>, dim3((unsigned)((total4 + 63) / 64)), dim3(256), 0, s, partial,
+                               p.n_partial, n_rows, c.d_model, (__bf16 *)y_perm);
+        else
+            hipLaunchKernelGGL(ffn_reduce_kernel<16>, dim3((unsigned)((total4 + 15) / 16)), dim3(256), 0, s, partial,
+                               p.n_partial, n_rows, c.d_model, (__bf16 *)y_perm);
         PG_HIP(ctx, hipGetLastError());
     }
     return PGMOE_OK;
