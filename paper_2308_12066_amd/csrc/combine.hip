@@ -48,6 +48,85 @@ __global__ __launch_bounds__(256) void combine_kernel(const XT *__restrict__ y_p
     }
 }
 
+// Combine straight from the FFN's unreduced float32 partials: for every selected row the P
+// partials are added exactly as ffn_reduce_kernel<PL> adds them (PL interleaved sub-sums, then
+// the sub-sums in ascending order), rounded to bf16 as y_perm would have been, and only then
+// weighted and accumulated, so the result is bit-identical to reduce + combine.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+template <int PL>
+__global__ __launch_bounds__(256) void combine_partials_kernel(const float *__restrict__ partial, int P, int n_rows,
+                                                                const int32_t *__restrict__ row_of,
+                                                                const float *__restrict__ prob, int d, int k,
+                                                                __bf16 *__restrict__ y, const __bf16 *__restrict__ x_res,
+                                                                __bf16 *__restrict__ x_next) {
+    // 256 threads = PL p-lanes x COLS float4 columns of one token (same split as ffn_reduce_kernel<PL>)
+    constexpr int COLS = 256 / PL;
+    __shared__ floatx4 sub[PL][COLS + 1];
+    const int t = blockIdx.x;
+    const int col = threadIdx.x % COLS, pl = threadIdx.x / COLS;
+    const int c4 = blockIdx.y * COLS + col;
+    const bool live = c4 < d / 4;
+    const size_t plane4 = (size_t)n_rows * d / 4;
+    floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < k; ++j) {
+        floatx4 s = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (live) {
+            const floatx4 *src = reinterpret_cast<const floatx4 *>(partial) + (size_t)row_of[(size_t)t * k + j] * (d / 4) + c4;
+            for (int p = pl; p < P; p += PL) s += src[(size_t)p * plane4];
+        }
+        if (PL > 1) {
+            __syncthreads();  // previous round's readers are done with sub
+            sub[pl][col] = s;
+            __syncthreads();
+            if (pl == 0) {
+                s = sub[0][col];
+#pragma unroll
+                for (int l = 1; l < PL; ++l) s += sub[l][col];
+            }
+        }
+        if (pl == 0) {
+            const float p = prob[(size_t)t * k + j];
+            acc.x = fmaf(p, (float)(__bf16)s.x, acc.x);
+            acc.y = fmaf(p, (float)(__bf16)s.y, acc.y);
+            acc.z = fmaf(p, (float)(__bf16)s.z, acc.z);
+            acc.w = fmaf(p, (float)(__bf16)s.w, acc.w);
+        }
+    }
+    if (pl != 0 || !live) return;
+    const size_t o = (size_t)t * d + 4 * (size_t)c4;
+    if (y) {
+        bf16x4 v;
+        v.x = (__bf16)acc.x; v.y = (__bf16)acc.y; v.z = (__bf16)acc.z; v.w = (__bf16)acc.w;
+        *reinterpret_cast<bf16x4 *>(y + o) = v;
+    }
+    if (x_next) {
+        const bf16x4 r = *reinterpret_cast<const bf16x4 *>(x_res + o);
+        bf16x4 v;
+        v.x = (__bf16)((float)r.x + acc.x); v.y = (__bf16)((float)r.y + acc.y);
+        v.z = (__bf16)((float)r.z + acc.z); v.w = (__bf16)((float)r.w + acc.w);
+        *reinterpret_cast<bf16x4 *>(x_next + o) = v;
+    }
+}
+
+int launch_combine_partials(pgmoe_ctx *ctx, const float *partial, int P, int n_rows, const int32_t *row_of,
+                            const float *prob, int T, void *y, const void *x_res, void *x_next, hipStream_t s) {
+    const pgmoe_config &c = ctx->cfg;
+    const int pl = reduce_lanes(P);
+    const int cols = 256 / pl;
+    const dim3 grid(T, (c.d_model / 4 + cols - 1) / cols);
+#define PG_CP(PL_)                                                                                                   \
+    hipLaunchKernelGGL(combine_partials_kernel<PL_>, grid, dim3(256), 0, s, partial, P, n_rows, row_of, prob, c.d_model, \
+                       c.top_k, (__bf16 *)y, (const __bf16 *)x_res, (__bf16 *)x_next)
+    if (pl == 1) PG_CP(1);
+    else if (pl == 4) PG_CP(4);
+    else PG_CP(16);
+#undef PG_CP
+    PG_HIP(ctx, hipGetLastError());
+    return PGMOE_OK;
+}
+
 template <typename XT>
 static void launch_t(const pgmoe_config &c, const void *y_perm, const int32_t *row_of, const float *prob, int T, void *y,
                      const void *x_res, void *x_next, hipStream_t s) {

@@ -273,8 +273,10 @@ int pgmoe_slot_address(pgmoe_ctx *ctx, int block, int slot, void **dev_out) {
     return PGMOE_OK;
 }
 
-int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_t *expert_offsets, int n_rows,
-                     void *y_perm, void *workspace, void *stream) {
+// pgmoe_expert_ffn with the option to leave the float32 partial sums unreduced in the workspace
+// (keep_partials != NULL; see launch_ffn), which pgmoe_stack_step feeds to the fused combine.
+static int expert_ffn_impl(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_t *expert_offsets, int n_rows,
+                           void *y_perm, void *workspace, void *stream, int *keep_partials) {
     const char *fn = "pgmoe_expert_ffn";
     if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
     int rc = check_block(ctx, fn, block);
@@ -289,7 +291,7 @@ int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_
     hipStream_t s = (hipStream_t)stream;
     if (ctx->store_mode == STORE_RESIDENT)
         return launch_ffn(ctx, ctx->store_base + (size_t)block * ctx->block_stride, ctx->expert_stride, false,
-                          ctx->cfg.n_experts, x_perm, expert_offsets, n_rows, y_perm, workspace, s);
+                          ctx->cfg.n_experts, x_perm, expert_offsets, n_rows, y_perm, workspace, s, keep_partials);
     const int gen = block & 1;
     if (ctx->fetched_block[gen] != block)
         return fail(ctx, PGMOE_ESTATE, "%s: block %d was not fetched (generation holds block %d)", fn, block, ctx->fetched_block[gen]);
@@ -297,11 +299,16 @@ int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_
     if (ctx->fetch_stream[gen] != s) PG_HIP(ctx, hipStreamWaitEvent(s, ctx->fetch_done[gen], 0));
     if (ctx->trace) PG_HIP(ctx, hipEventRecord(ctx->ev_waited[block], s));
     rc = launch_ffn(ctx, ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes, ctx->expert_bytes, true, ctx->slots,
-                    x_perm, expert_offsets, n_rows, y_perm, workspace, s);
+                    x_perm, expert_offsets, n_rows, y_perm, workspace, s, keep_partials);
     if (rc) return rc;
     ctx->ffn_recorded[gen] = true;
     ctx->ffn_stream[gen] = s;
     return PGMOE_OK;
+}
+
+int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_t *expert_offsets, int n_rows,
+                     void *y_perm, void *workspace, void *stream) {
+    return expert_ffn_impl(ctx, block, x_perm, expert_offsets, n_rows, y_perm, workspace, stream, nullptr);
 }
 
 int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *compute_stream, void *copy_stream) {
@@ -359,10 +366,17 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
         int32_t *offs = io->expert_offsets + (size_t)i * (c.n_experts + 1);
         rc = pgmoe_permute(ctx, x_at(i), idx_at(i), T, io->x_perm, row_of, offs, compute_stream);
         if (rc) return rc;
-        rc = pgmoe_expert_ffn(ctx, i, io->x_perm, offs, (int)nk, io->y_perm, io->workspace, compute_stream);
+        // FFN, then the weighted combine; when the FFN left float32 partial sums, the combine
+        // kernel adds them itself (same order as the stand-alone reduction) and y_perm is skipped
+        int n_partial = 0;
+        rc = expert_ffn_impl(ctx, i, io->x_perm, offs, (int)nk, io->y_perm, io->workspace, compute_stream, &n_partial);
         if (rc) return rc;
         void *y = io->y_blocks ? (char *)io->y_blocks + (size_t)i * xbytes : nullptr;
-        rc = pgmoe_combine(ctx, io->y_perm, row_of, prob_at(i), T, y, x_at(i), x_at(i + 1), compute_stream);
+        if (n_partial > 0)
+            rc = launch_combine_partials(ctx, (const float *)io->workspace, n_partial, (int)nk, row_of, prob_at(i), T, y,
+                                         x_at(i), x_at(i + 1), (hipStream_t)compute_stream);
+        else
+            rc = pgmoe_combine(ctx, io->y_perm, row_of, prob_at(i), T, y, x_at(i), x_at(i + 1), compute_stream);
         if (rc) return rc;
         if (ctx->trace) {
             PG_HIP(ctx, hipEventRecord(ctx->ev_c1[i], (hipStream_t)compute_stream));

@@ -252,6 +252,7 @@ __global__ __launch_bounds__(256) void ffn_reduce_kernel(const float *__restrict
         const floatx4 *src = reinterpret_cast<const floatx4 *>(partial) + i;
         for (int p = pl; p < P; p += PL) s += src[(size_t)p * total4];
     }
+    static_assert(PL == 1 || PL == 4 || PL == 16, "keep in step with reduce_lanes()");
     if (PL > 1) {
         sub[pl][col] = s;
         __syncthreads();
@@ -394,7 +395,7 @@ static int timing_slot(pgmoe_ctx *ctx) {
 template <int MT, int KT, int NW, int D>
 static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots,
                         const void *x_perm, const int32_t *offsets, int n_rows, void *y_perm, void *workspace,
-                        hipStream_t s) {
+                        hipStream_t s, int *keep_partials) {
     const pgmoe_config &c = ctx->cfg;
     const size_t lds = (size_t)MT * KT * 1024 + 2u * MT * (16 * NW / 32) * 1024;
     auto kern = ffn_fused_kernel<MT, KT, NW, D>;
@@ -413,12 +414,17 @@ static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, si
                        n_rows);
     PG_HIP(ctx, hipGetLastError());
     if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
+    if (keep_partials) {
+        *keep_partials = partial ? p.n_partial : 0;
+        return PGMOE_OK;
+    }
     if (partial) {
         const size_t total4 = (size_t)n_rows * c.d_model / 4;
-        if (p.n_partial <= 2)
+        const int pl = reduce_lanes(p.n_partial);
+        if (pl == 1)
             hipLaunchKernelGGL(ffn_reduce_kernel<1>, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, partial,
                                p.n_partial, n_rows, c.d_model, (__bf16 *)y_perm);
-        else if (p.n_partial <= 8)
+        else if (pl == 4)
             hipLaunchKernelGGL(ffn_reduce_kernel<4>, dim3((unsigned)((total4 + 63) / 64)), dim3(256), 0, s, partial,
                                p.n_partial, n_rows, c.d_model, (__bf16 *)y_perm);
         else
@@ -430,8 +436,9 @@ static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, si
 }
 
 int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots, const void *x_perm,
-               const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s) {
+               const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s, int *keep_partials) {
     const pgmoe_config &c = ctx->cfg;
+    if (keep_partials) *keep_partials = 0;
     if (n_rows == 0) return PGMOE_OK;
     if (c.dtype == PGMOE_F32) {
         float *h = (float *)workspace;
@@ -451,7 +458,7 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
     const int kt = c.d_model / 32;
     if (c.d_ff % (16 * p.nw)) return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: d_ff=%d is not a multiple of the %d-column sub-slab", c.d_ff, 16 * p.nw);
 #define PG_CASE(MT_, KT_, NW_, D_) \
-    if (p.mt == MT_ && kt == KT_ && p.nw == NW_) return launch_fused<MT_, KT_, NW_, D_>(ctx, p, w_base, w_stride, slot_by_rank, n_slots, x_perm, offsets, n_rows, y_perm, workspace, s)
+    if (p.mt == MT_ && kt == KT_ && p.nw == NW_) return launch_fused<MT_, KT_, NW_, D_>(ctx, p, w_base, w_stride, slot_by_rank, n_slots, x_perm, offsets, n_rows, y_perm, workspace, s, keep_partials)
     PG_CASE(1, 2, 4, 4); PG_CASE(1, 4, 4, 8); PG_CASE(1, 8, 4, 16); PG_CASE(1, 16, 4, 16); PG_CASE(1, 24, 4, 16);
     PG_CASE(1, 32, 4, 16); PG_CASE(1, 64, 4, 16); PG_CASE(1, 24, 2, 24); PG_CASE(1, 32, 2, 24);
     PG_CASE(2, 2, 4, 4); PG_CASE(2, 4, 4, 8); PG_CASE(2, 8, 4, 16); PG_CASE(2, 16, 4, 16); PG_CASE(2, 24, 4, 16);

@@ -110,8 +110,16 @@ int launch_gate(pgmoe_ctx *ctx, const void *x, const void *w, const float *bias,
                 float *prob, float *probs, hipStream_t s);
 int launch_permute(pgmoe_ctx *ctx, const void *x, const int32_t *idx, int T, void *x_perm,
                    int32_t *row_of, int32_t *offsets, hipStream_t s);
+// keep_partials != nullptr: if the launch produces float32 partial sums, leave them in the
+// workspace unreduced and report their number there (0 = y_perm was written directly).
 int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots, const void *x_perm,
-               const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s);
+               const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s, int *keep_partials = nullptr);
+// p-lanes of the partial-sum reduction for P partials (fixes the order of the additions)
+inline int reduce_lanes(int P) { return P <= 2 ? 1 : (P <= 8 ? 4 : 16); }
+// Combine straight from P unreduced float32 partials [P][n_rows][d] (bf16 contexts only): same
+// arithmetic, in the same order, as ffn_reduce_kernel followed by launch_combine.
+int launch_combine_partials(pgmoe_ctx *ctx, const float *partial, int P, int n_rows, const int32_t *row_of,
+                            const float *prob, int T, void *y, const void *x_res, void *x_next, hipStream_t s);
 int launch_fetch_pull(pgmoe_ctx *ctx, int block, const int32_t *idx, int n, hipStream_t s);
 int launch_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, const float *prob, int T,
                    void *y, const void *x_res, void *x_next, hipStream_t s);

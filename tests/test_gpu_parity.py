@@ -452,3 +452,44 @@ def test_pull_fetch_with_too_few_slots_flags_and_zeroes(hx):
     for e in (5, 6):
         assert np.all(y[r["offsets"][e]: r["offsets"][e + 1]] == 0.0)
     ctx.close()
+
+
+@pytest.mark.parametrize("dtype,T,d,f,E,k,L,offloaded", [
+    ("bf16", 40, 128, 256, 16, 2, 4, True), ("bf16", 1, 768, 3072, 8, 1, 3, True), ("bf16", 300, 256, 512, 8, 1, 3, False),
+    ("f32", 32, 64, 256, 8, 1, 2, False),
+])
+def test_stack_step_equals_the_primitive_call_sequence(hx, dtype, T, d, f, E, k, L, offloaded):
+    """pgmoe_stack_step (which fuses the partial-sum reduction into the combine and orders the
+    fetches itself) must give bit-identical hidden states to the five primitives called one by
+    one in the paper's order: pre-gate i on x_i routes block i+1; block 0 has its own gate."""
+    H, B = hx
+    w = W.Workload("seq_case", 80, L, d, f, E, k, T, 1, dtype, 0.0, offloaded)
+    stack, gates, cache = make_stack(H, w, threads=4)
+    stack.set_input(W.step_input(w, 0))
+    stack.step()
+    torch.cuda.synchronize()
+    ctx = stack.ctx
+    xs = [stack.x_states[0].clone()]
+    idx = torch.zeros((L, T, k), dtype=torch.int32, device="cuda")
+    prob = torch.zeros((L, T, k), dtype=torch.float32, device="cuda")
+    x_perm, y_perm = torch.zeros_like(stack.x_perm), torch.zeros_like(stack.y_perm)
+    row_of = torch.zeros(T * k, dtype=torch.int32, device="cuda")
+    offs = torch.zeros(E + 1, dtype=torch.int32, device="cuda")
+    comp, copy = stack.compute, stack.copy
+    ctx.pregate_topk(xs[0], stack.gate_w[0], stack.gate_b[0], T, idx[0], prob[0], None, comp)
+    ctx.fetch_experts(0, idx[0], T, comp, copy)
+    for i in range(L):
+        if i + 1 < L:
+            ctx.pregate_topk(xs[i], stack.gate_w[i + 1], stack.gate_b[i + 1], T, idx[i + 1], prob[i + 1], None, comp)
+            ctx.fetch_experts(i + 1, idx[i + 1], T, comp, copy)
+        ctx.permute(xs[i], idx[i], T, x_perm, row_of, offs, comp)
+        ctx.expert_ffn(i, x_perm, offs, T * k, y_perm, stack.workspace, comp)
+        y = torch.zeros_like(xs[i])
+        xn = torch.zeros_like(xs[i])
+        ctx.combine(y_perm, row_of, prob[i], T, y, xs[i], xn, comp)
+        torch.cuda.synchronize()
+        assert torch.equal(idx[i], stack.topk_idx[i]) and torch.equal(prob[i], stack.topk_prob[i])
+        assert torch.equal(y, stack.y_blocks[i]), f"block {i}: y differs between stack_step and the primitives"
+        assert torch.equal(xn, stack.x_states[i + 1])
+        xs.append(xn)
+    stack.close()
