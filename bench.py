@@ -99,7 +99,7 @@ def pmc_traffic(workload_name):
         return None
 
 
-def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gpu_only=True):
+def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gpu_only=True, systems=False):
     import numpy as np
     import torch
 
@@ -245,6 +245,43 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
                            "note": "same workload and routing with all experts resident in HBM (no migration)"}
         stack2.close()
         del stack2, bufs2
+    if w.offloaded and systems:
+        # The paper's comparison systems on the same kernels and the same workload (conventional
+        # wiring): experts fetched on demand after the gate, or all experts of the next block
+        # prefetched.  Block latency is what the paper's latency figure compares.
+        from paper_2308_12066_amd import binding as B
+        Ks = min(K, 32)
+        comp = {"pregated": {"block_latency_us": 1e6 * dt / (K * L), "tokens_per_s": T * K / dt,
+                             "peak_resident_expert_MB": float((uniq[:, :-1] + uniq[:, 1:]).max() if L > 1 else uniq.max())
+                             * w.expert_bytes / 1e6}}
+        for sname, sched in (("on_demand", B.SCHED_ON_DEMAND), ("prefetch_all", B.SCHED_PREFETCH_ALL)):
+            stk = H.Stack(w, store, slots_per_gen=E if sched == B.SCHED_PREFETCH_ALL else 0)
+            stk.ctx.set_schedule(sched)
+            bufs = [stk.ctx.make_step_buffers(stk.gate_w, stk.gate_b, x_all[s % n_in], stk.y_blocks, idx_log[s],
+                                              stk.topk_prob, stk.row_of, stk.expert_offsets, stk.x_perm, stk.y_perm,
+                                              stk.workspace) for s in range(Ks)]
+            for s in range(2):
+                stk.ctx.stack_step(bufs[s], T, stk.compute, stk.copy)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for s in range(Ks):
+                stk.ctx.stack_step(bufs[s], T, stk.compute, stk.copy)
+            torch.cuda.synchronize()
+            dts = time.perf_counter() - t0
+            u2 = np.array([[len(np.unique(r)) for r in step] for step in idx_log[:Ks].cpu().numpy()])
+            peak = 2 * E if sched == B.SCHED_PREFETCH_ALL else int(u2.max())
+            comp[sname] = {"block_latency_us": 1e6 * dts / (Ks * L), "tokens_per_s": T * Ks / dts,
+                           "peak_resident_expert_MB": peak * w.expert_bytes / 1e6}
+            stk.close()
+            del stk, bufs
+        if "gpu_only" in out:
+            comp["gpu_only"] = {"block_latency_us": 1e3 * out["gpu_only"]["ms_per_step"] / L,
+                                "tokens_per_s": out["gpu_only"]["value"],
+                                "peak_resident_expert_MB": L * E * w.expert_bytes / 1e6}
+        base = comp["pregated"]["block_latency_us"]
+        for v in comp.values():
+            v["block_latency_vs_pregated"] = v["block_latency_us"] / base
+        out["systems"] = comp
     if with_cpu:
         sample = cpu_steps or max(1, min(K, int(round(600.0 / (T * L * k)))))
         log(f"[bench] {w.name}: timing the CPU oracle on {sample} steps")
@@ -275,7 +312,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
     out = run_workload(args.workload, args.steps, args.warmup, args.host_threads, not args.no_cpu_baseline,
-                       args.cpu_sample_steps, args.trace_steps)
+                       args.cpu_sample_steps, args.trace_steps, systems=True)
     out["measured_peaks"] = measured_peaks()
     others = [n for n in args.also.split(",") if n and n != args.workload]
     if args.all:

@@ -158,6 +158,11 @@ int pgmoe_register_resident_experts(pgmoe_ctx *ctx, const void *dev_base, size_t
  * n_unique_out host | NULL. */
 int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int T,
                         void *compute_stream, void *copy_stream, int *n_unique_out);
+/* Copy EVERY expert of `block` into the block's generation, slot = expert id (what the
+ * prefetch-all comparison system of the paper migrates; Sec. III "Prefetch-all").  Needs
+ * slots_per_gen == n_experts.  Ordering as pgmoe_fetch_experts, except that there are no
+ * indices to wait for: the copy is ordered behind everything queued on compute_stream so far. */
+int pgmoe_fetch_all_experts(pgmoe_ctx *ctx, int block, void *compute_stream, void *copy_stream);
 int pgmoe_get_fetch_stats(pgmoe_ctx *ctx, int block, pgmoe_fetch_stats *out /* host */);
 /* Bracket every following fetch with a pair of timing events on the copy stream (fetch_ms of
  * pgmoe_fetch_stats).  Off by default: each event record costs microseconds between the
@@ -216,6 +221,17 @@ int pgmoe_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, con
  * gate_w[0] / gate_b[0] is block 0's conventional gate, gate_w[g] / gate_b[g] for g >= 1 the
  * pre-gate that sits in block g-1 (routes block g).  Arrays of pointers are host arrays of
  * device pointers; gate_b or any gate_b[g] may be NULL. */
+/* Schedules of pgmoe_stack_step.  PREGATED is the paper's method and the default.  The other
+ * two are the paper's comparison systems on the same kernels (Sec. III and the timeline figure
+ * of Sec. IV-C): conventional wiring, i.e. gate_w[g] is block g's own gate applied to x_g, with
+ *   ON_DEMAND    gate_i -> migrate the selected experts -> FFN_i, serially;
+ *   PREFETCH_ALL all E experts of block i+1 migrate while block i executes (slots_per_gen = E).
+ * With a resident expert store nothing migrates and either gives the GPU-only design point. */
+#define PGMOE_SCHED_PREGATED 0
+#define PGMOE_SCHED_ON_DEMAND 1
+#define PGMOE_SCHED_PREFETCH_ALL 2
+int pgmoe_set_schedule(pgmoe_ctx *ctx, int schedule);
+
 typedef struct {
     const void *const *gate_w;  /* host [L] -> dev [d,E] */
     const float *const *gate_b; /* host [L] -> dev [E] | NULL; may itself be NULL */

@@ -17,6 +17,7 @@ OK, EINVAL, ENOTPINNED, ENOSLOT, EBADINDEX, EHIP, ENODEVICE, ESTATE = 0, -1, -2,
 F32, BF16 = 0, 1
 FLAG_HOST_ONLY = 1
 FLAG_FETCH_MEMCPY = 2
+SCHED_PREGATED, SCHED_ON_DEMAND, SCHED_PREFETCH_ALL = 0, 1, 2
 MAX_EXPERTS = 256
 
 EXPORTS = [
@@ -24,7 +25,7 @@ EXPORTS = [
     "pgmoe_pack_expert", "pgmoe_unpack_expert", "pgmoe_pregate_topk", "pgmoe_register_host_experts",
     "pgmoe_register_resident_experts", "pgmoe_fetch_experts", "pgmoe_get_fetch_stats", "pgmoe_unique_experts",
     "pgmoe_permute", "pgmoe_expert_ffn", "pgmoe_combine", "pgmoe_stack_step", "pgmoe_device_flags",
-    "pgmoe_ffn_timing_begin", "pgmoe_ffn_timing_end", "pgmoe_slot_address", "pgmoe_fetch_timing", "pgmoe_trace", "pgmoe_get_block_trace",
+    "pgmoe_ffn_timing_begin", "pgmoe_ffn_timing_end", "pgmoe_slot_address", "pgmoe_fetch_timing", "pgmoe_trace", "pgmoe_get_block_trace", "pgmoe_fetch_all_experts", "pgmoe_set_schedule",
 ]
 
 
@@ -85,6 +86,8 @@ def _load():
     L.pgmoe_ffn_timing_begin.argtypes = [vp, i]
     L.pgmoe_fetch_timing.argtypes = [vp, i]
     L.pgmoe_trace.argtypes = [vp, i]
+    L.pgmoe_fetch_all_experts.argtypes = [vp, i, vp, vp]
+    L.pgmoe_set_schedule.argtypes = [vp, i]
     L.pgmoe_get_block_trace.argtypes = [vp, i, POINTER(BlockTrace)]
     L.pgmoe_slot_address.argtypes = [vp, i, i, POINTER(vp)]
     L.pgmoe_ffn_timing_end.argtypes = [vp, POINTER(c_int), POINTER(c_float), POINTER(c_float)]
@@ -261,3 +264,9 @@ class Context:
         t = BlockTrace()
         self._check(lib.pgmoe_get_block_trace(self._h, block, byref(t)))
         return t
+
+    def fetch_all_experts(self, block, compute_stream, copy_stream):
+        self._check(lib.pgmoe_fetch_all_experts(self._h, block, _stream(compute_stream), _stream(copy_stream)))
+
+    def set_schedule(self, schedule: int):
+        self._check(lib.pgmoe_set_schedule(self._h, schedule))

@@ -93,23 +93,26 @@ int pgmoe_register_resident_experts(pgmoe_ctx *ctx, const void *dev_base, size_t
     return PGMOE_OK;
 }
 
-int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int T, void *compute_stream,
-                        void *copy_stream, int *n_unique_out) {
-    const char *fn = "pgmoe_fetch_experts";
+// Shared body of pgmoe_fetch_experts (all == false: the experts topk_idx selects) and
+// pgmoe_fetch_all_experts (all == true: every expert of the block, slot = expert id).
+static int fetch_impl(pgmoe_ctx *ctx, const char *fn, int block, bool all, const int32_t *topk_idx, int T,
+                      void *compute_stream, void *copy_stream, int *n_unique_out) {
     if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
     int rc = check_block(ctx, fn, block);
     if (rc) return rc;
     if (T < 0 || T > ctx->cfg.max_tokens) return fail(ctx, PGMOE_EINVAL, "%s: T=%d outside 0..max_tokens=%d", fn, T, ctx->cfg.max_tokens);
-    if (!topk_idx) return fail(ctx, PGMOE_EINVAL, "%s: topk_idx is NULL", fn);
-    if (!aligned(topk_idx, 4)) return fail(ctx, PGMOE_EINVAL, "%s: topk_idx is not 4-byte aligned", fn);
+    if (!all && !topk_idx) return fail(ctx, PGMOE_EINVAL, "%s: topk_idx is NULL", fn);
+    if (!all && !aligned(topk_idx, 4)) return fail(ctx, PGMOE_EINVAL, "%s: topk_idx is not 4-byte aligned", fn);
     if (ctx->store_mode == STORE_NONE) return fail(ctx, PGMOE_ESTATE, "%s: no expert store registered", fn);
     if (ctx->store_mode == STORE_RESIDENT) {
         if (n_unique_out) *n_unique_out = -1;
         return PGMOE_OK;
     }
+    if (all && ctx->slots < ctx->cfg.n_experts)
+        return fail(ctx, PGMOE_ENOSLOT, "%s: fetching all %d experts needs slots_per_gen = n_experts (have %d)", fn, ctx->cfg.n_experts, ctx->slots);
     if (ctx->host_only) return fail(ctx, PGMOE_ENODEVICE, "%s: context is host-only, nothing can be launched", fn);
     hipStream_t cs = (hipStream_t)compute_stream, ps = (hipStream_t)copy_stream;
-    const int n = T * ctx->cfg.top_k;
+    const int n = all ? 0 : T * ctx->cfg.top_k;
     const int gen = block & 1;
     const bool inline_fetch = ps == cs;  // exposed fetch on the compute stream itself: plain stream order
     if (!inline_fetch && gen == 0 && block > 1) ps = ctx->copy2;  // blocks 0,1 queue on the caller's stream, then alternate
@@ -126,11 +129,12 @@ int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int 
         rc = wait_for_last_reader(ctx, gen, cs, ps);
         if (rc) return rc;
         if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_begin[block], ps));
-        rc = launch_fetch_pull(ctx, block, topk_idx, n, ps);
+        rc = launch_fetch_pull(ctx, block, all, topk_idx, n, ps);
         if (rc) return rc;
         if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_end[block], ps));
         if (!inline_fetch) PG_HIP(ctx, hipEventRecord(ctx->fetch_done[gen], ps));
         ctx->fetch_stream[gen] = ps;
+        ctx->gen_all[gen] = all;
         ctx->fetched_block[gen] = block;
         ctx->live_slots[gen] = -1;  // known on the device only
         st.timed = ctx->fetch_timing;
@@ -147,6 +151,11 @@ int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int 
 
     // 1. bring the indices to the host (the only host wait of the block)
     const auto t0 = std::chrono::steady_clock::now();
+    if (all && !inline_fetch) {
+        // no indices to wait for: order the copies behind what is queued on the compute stream
+        PG_HIP(ctx, hipEventRecord(ctx->idx_ready, cs));
+        PG_HIP(ctx, hipStreamWaitEvent(ps, ctx->idx_ready, 0));
+    }
     if (n > 0) {
         PG_HIP(ctx, hipMemcpyAsync(ctx->idx_staging, topk_idx, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, cs));
         PG_HIP(ctx, hipEventRecord(ctx->idx_ready, cs));
@@ -159,7 +168,11 @@ int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int 
 
     // 2. distinct experts, ascending; slot j <- j-th of them
     int32_t uniq[PGMOE_MAX_EXPERTS];
-    const int nu = pgmoe_unique_experts(ctx->idx_staging, n, ctx->cfg.n_experts, uniq);
+    int nu = ctx->cfg.n_experts;
+    if (all)
+        for (int e = 0; e < nu; ++e) uniq[e] = e;
+    else
+        nu = pgmoe_unique_experts(ctx->idx_staging, n, ctx->cfg.n_experts, uniq);
     if (nu < 0) return fail(ctx, nu, "%s: %s", fn, pgmoe_last_error(nullptr));
     if (nu > ctx->slots) return fail(ctx, PGMOE_ENOSLOT, "%s: %d distinct experts selected but only %d slots per generation", fn, nu, ctx->slots);
 
@@ -176,6 +189,7 @@ int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int 
     if (!inline_fetch) PG_HIP(ctx, hipEventRecord(ctx->fetch_done[gen], ps));
 
     ctx->fetch_stream[gen] = ps;
+    ctx->gen_all[gen] = all;
     ctx->fetched_block[gen] = block;
     ctx->live_slots[gen] = nu;
     st.timed = ctx->fetch_timing;
@@ -186,6 +200,23 @@ int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int 
     // runs (block - 1); anything else in it is left over from an earlier pass
     st.s.resident_slots = nu + (ctx->fetched_block[gen ^ 1] == block - 1 ? ctx->live_slots[gen ^ 1] : 0);
     if (n_unique_out) *n_unique_out = nu;
+    return PGMOE_OK;
+}
+
+int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int T, void *compute_stream,
+                        void *copy_stream, int *n_unique_out) {
+    return fetch_impl(ctx, "pgmoe_fetch_experts", block, false, topk_idx, T, compute_stream, copy_stream, n_unique_out);
+}
+
+int pgmoe_fetch_all_experts(pgmoe_ctx *ctx, int block, void *compute_stream, void *copy_stream) {
+    return fetch_impl(ctx, "pgmoe_fetch_all_experts", block, true, nullptr, 0, compute_stream, copy_stream, nullptr);
+}
+
+int pgmoe_set_schedule(pgmoe_ctx *ctx, int schedule) {
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "pgmoe_set_schedule: ctx is NULL");
+    if (schedule < PGMOE_SCHED_PREGATED || schedule > PGMOE_SCHED_PREFETCH_ALL)
+        return fail(ctx, PGMOE_EINVAL, "pgmoe_set_schedule: unknown schedule %d", schedule);
+    ctx->schedule = schedule;
     return PGMOE_OK;
 }
 
@@ -298,8 +329,9 @@ static int expert_ffn_impl(pgmoe_ctx *ctx, int block, const void *x_perm, const 
     if (ctx->trace) PG_HIP(ctx, hipEventRecord(ctx->ev_ready[block], s));
     if (ctx->fetch_stream[gen] != s) PG_HIP(ctx, hipStreamWaitEvent(s, ctx->fetch_done[gen], 0));
     if (ctx->trace) PG_HIP(ctx, hipEventRecord(ctx->ev_waited[block], s));
-    rc = launch_ffn(ctx, ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes, ctx->expert_bytes, true, ctx->slots,
-                    x_perm, expert_offsets, n_rows, y_perm, workspace, s, keep_partials);
+    // a generation filled by pgmoe_fetch_all_experts is indexed by expert id, else by rank
+    rc = launch_ffn(ctx, ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes, ctx->expert_bytes, !ctx->gen_all[gen],
+                    ctx->slots, x_perm, expert_offsets, n_rows, y_perm, workspace, s, keep_partials);
     if (rc) return rc;
     ctx->ffn_recorded[gen] = true;
     ctx->ffn_stream[gen] = s;
@@ -334,6 +366,51 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     auto prob_at = [&](int i) { return io->topk_prob + (size_t)i * nk; };
     auto bias_at = [&](int g) -> const float * { return io->gate_b ? io->gate_b[g] : nullptr; };
     int rc;
+
+    if (ctx->schedule != PGMOE_SCHED_PREGATED) {
+        // Conventional MoE wiring (Sec. II-B; the paper's comparison systems of Sec. III / Fig.
+        // "timeline"): gate g routes block g from the block's own input.  ON_DEMAND migrates the
+        // selected experts after the gate, serially; PREFETCH_ALL migrates every expert of block
+        // i+1 while block i executes.  With a resident store both are the GPU-only design point.
+        const bool host = ctx->store_mode == STORE_HOST;
+        const bool prefetch = ctx->schedule == PGMOE_SCHED_PREFETCH_ALL;
+        if (host && prefetch) {
+            rc = pgmoe_fetch_all_experts(ctx, 0, compute_stream, copy_stream);
+            if (rc) return rc;
+        }
+        for (int i = 0; i < L; ++i) {
+            if (ctx->trace) PG_HIP(ctx, hipEventRecord(ctx->ev_c0[i], (hipStream_t)compute_stream));
+            rc = pgmoe_pregate_topk(ctx, x_at(i), io->gate_w[i], bias_at(i), T, idx_at(i), prob_at(i), nullptr, compute_stream);
+            if (rc) return rc;
+            if (host && !prefetch) {
+                rc = pgmoe_fetch_experts(ctx, i, idx_at(i), T, compute_stream, ctx->pull ? compute_stream : copy_stream, nullptr);
+                if (rc) return rc;
+            }
+            if (host && prefetch && i + 1 < L) {
+                rc = pgmoe_fetch_all_experts(ctx, i + 1, compute_stream, copy_stream);
+                if (rc) return rc;
+            }
+            int32_t *row_of = io->row_of + (size_t)i * nk;
+            int32_t *offs = io->expert_offsets + (size_t)i * (c.n_experts + 1);
+            rc = pgmoe_permute(ctx, x_at(i), idx_at(i), T, io->x_perm, row_of, offs, compute_stream);
+            if (rc) return rc;
+            int n_partial = 0;
+            rc = expert_ffn_impl(ctx, i, io->x_perm, offs, (int)nk, io->y_perm, io->workspace, compute_stream, &n_partial);
+            if (rc) return rc;
+            void *y = io->y_blocks ? (char *)io->y_blocks + (size_t)i * xbytes : nullptr;
+            if (n_partial > 0)
+                rc = launch_combine_partials(ctx, (const float *)io->workspace, n_partial, (int)nk, row_of, prob_at(i), T, y,
+                                             x_at(i), x_at(i + 1), (hipStream_t)compute_stream);
+            else
+                rc = pgmoe_combine(ctx, io->y_perm, row_of, prob_at(i), T, y, x_at(i), x_at(i + 1), compute_stream);
+            if (rc) return rc;
+            if (ctx->trace) {
+                PG_HIP(ctx, hipEventRecord(ctx->ev_c1[i], (hipStream_t)compute_stream));
+                ctx->traced[i] = host && ctx->fetch_timing;
+            }
+        }
+        return PGMOE_OK;
+    }
 
     if (ctx->trace) PG_HIP(ctx, hipEventRecord(ctx->ev_c0[0], (hipStream_t)compute_stream));
     // Block 0: its own (conventional) gate and, on the same input, pre-gate 0 for block 1.  Both

@@ -22,12 +22,13 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 template <typename V>
 __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_kernel(
     const int32_t *__restrict__ idx, int n, int E, const char *__restrict__ src_block, size_t expert_stride,
-    char *__restrict__ gen_base, size_t expert_bytes, int slots, int32_t *__restrict__ unique_out, uint32_t *flags) {
+    char *__restrict__ gen_base, size_t expert_bytes, int slots, int all, int32_t *__restrict__ unique_out,
+    uint32_t *flags) {
     __shared__ int present[PGMOE_MAX_EXPERTS];
     __shared__ int list[PGMOE_MAX_EXPERTS];
     __shared__ int s_u;
     const int tid = threadIdx.x;
-    for (int e = tid; e < PGMOE_MAX_EXPERTS; e += FETCH_THREADS) present[e] = 0;
+    for (int e = tid; e < PGMOE_MAX_EXPERTS; e += FETCH_THREADS) present[e] = (all && e < E) ? 1 : 0;  // all: slot = expert id
     __syncthreads();
     bool bad = false;
     for (int i = tid; i < n; i += FETCH_THREADS) {
@@ -77,17 +78,17 @@ __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_kernel(
     }
 }
 
-int launch_fetch_pull(pgmoe_ctx *ctx, int block, const int32_t *idx, int n, hipStream_t s) {
+int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, int n, hipStream_t s) {
     const int gen = block & 1;
     char *gen_base = ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes;
     const char *src = ctx->store_dev + (size_t)block * ctx->block_stride;
     if (ctx->expert_bytes % 16 == 0)
         hipLaunchKernelGGL(fetch_pull_kernel<u32x4>, dim3(FETCH_GRID), dim3(FETCH_THREADS), 0, s, idx, n, ctx->cfg.n_experts,
-                           src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, ctx->dev_unique + block,
+                           src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, all ? 1 : 0, ctx->dev_unique + block,
                            ctx->dev_flags);
     else
         hipLaunchKernelGGL(fetch_pull_kernel<unsigned int>, dim3(FETCH_GRID), dim3(FETCH_THREADS), 0, s, idx, n,
-                           ctx->cfg.n_experts, src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots,
+                           ctx->cfg.n_experts, src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, all ? 1 : 0,
                            ctx->dev_unique + block, ctx->dev_flags);
     PG_HIP(ctx, hipGetLastError());
     return PGMOE_OK;

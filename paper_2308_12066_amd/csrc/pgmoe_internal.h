@@ -62,7 +62,9 @@ struct pgmoe_ctx {
     bool ffn_recorded[pgmoe::kGen];
     hipStream_t ffn_stream[pgmoe::kGen];    // stream the generation's last FFN ran on
     hipStream_t fetch_stream[pgmoe::kGen];  // stream the generation's last fetch ran on
-    hipStream_t copy2;                      // internal copy stream for odd generations
+    hipStream_t copy2;                      // internal second copy stream
+    bool gen_all[pgmoe::kGen];              // generation holds every expert of its block (slot = expert id)
+    int schedule;                           // PGMOE_SCHED_*
     bool fetch_timing;               // record fetch_begin / fetch_end
     bool trace;                      // record the per-block compute-stream events below
     hipEvent_t *ev_c0, *ev_ready, *ev_waited, *ev_c1;  // [n_blocks] each
@@ -120,7 +122,7 @@ inline int reduce_lanes(int P) { return P <= 2 ? 1 : (P <= 8 ? 4 : 16); }
 // arithmetic, in the same order, as ffn_reduce_kernel followed by launch_combine.
 int launch_combine_partials(pgmoe_ctx *ctx, const float *partial, int P, int n_rows, const int32_t *row_of,
                             const float *prob, int T, void *y, const void *x_res, void *x_next, hipStream_t s);
-int launch_fetch_pull(pgmoe_ctx *ctx, int block, const int32_t *idx, int n, hipStream_t s);
+int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, int n, hipStream_t s);
 int launch_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, const float *prob, int T,
                    void *y, const void *x_res, void *x_next, hipStream_t s);
 

@@ -269,7 +269,7 @@ def test_combine_matches_definition(hx, dtype, T, d, k):
 
 
 # ------------------------------------------------------------------------------ whole stack
-def check_stack_step(H, w, stack, gates, expert_cache, sample_tokens=None, label=""):
+def check_stack_step(H, w, stack, gates, expert_cache, sample_tokens=None, label="", wiring="pregated"):
     """Block-by-block check of one executed step against the oracle evaluated on the GPU's own
     hidden states (x_{i-1} routes block i, x_i feeds its experts).  Returns statistics."""
     torch.cuda.synchronize()
@@ -283,7 +283,7 @@ def check_stack_step(H, w, stack, gates, expert_cache, sample_tokens=None, label
     stats = dict(near_tie=0, tokens=0, max_err=0.0, max_prob_err=0.0)
     for i in range(L):
         gw, gb = gates[i]
-        o = R.gate(xs[R.routing_source(i)], gw, gb, k)
+        o = R.gate(xs[R.routing_source(i, wiring)], gw, gb, k)
         exact = o["gaps"].min(axis=1) >= TIE
         stats["near_tie"] += int((~exact).sum())
         stats["tokens"] += T
@@ -492,4 +492,33 @@ def test_stack_step_equals_the_primitive_call_sequence(hx, dtype, T, d, f, E, k,
         assert torch.equal(y, stack.y_blocks[i]), f"block {i}: y differs between stack_step and the primitives"
         assert torch.equal(xn, stack.x_states[i + 1])
         xs.append(xn)
+    stack.close()
+
+
+# ------------------------------------------------------------------------------ comparison schedules
+@pytest.mark.parametrize("schedule,fetch,offloaded", [
+    ("on_demand", "pull", True), ("on_demand", "memcpy", True), ("prefetch_all", "pull", True),
+    ("prefetch_all", "memcpy", True), ("on_demand", "-", False),
+])
+def test_comparison_schedules_match_the_conventional_oracle(hx, schedule, fetch, offloaded):
+    """The paper's comparison systems on the same kernels: conventional wiring (every block routed
+    by its own gate on its own input), experts fetched on demand or all prefetched; with a
+    resident store this is the GPU-only design point."""
+    H, B = hx
+    w = W.Workload("sched_case", 90, 4, 256, 512, 16, 2, 24, 1, "bf16", 1.1, offloaded)
+    stack, gates, cache = make_stack(H, w, threads=4, flags=B.FLAG_FETCH_MEMCPY if fetch == "memcpy" else 0)
+    stack.ctx.set_schedule(B.SCHED_ON_DEMAND if schedule == "on_demand" else B.SCHED_PREFETCH_ALL)
+    stack.ctx.fetch_timing(True)
+    for s in range(2):
+        stack.set_input(W.step_input(w, s))
+        stack.step()
+        st = check_stack_step(H, w, stack, gates, cache, label=f"{schedule} step {s}", wiring="conventional")
+        say(f"  {schedule}/{fetch} step {s}: {st}")
+        if offloaded:
+            for b in range(w.n_blocks):
+                fs = stack.ctx.fetch_stats(b)
+                u = len(np.unique(stack.topk_idx[b].cpu().numpy()))
+                expect = w.n_experts if schedule == "prefetch_all" else u
+                assert fs.n_copied == expect and fs.bytes_copied == expect * w.expert_bytes
+    assert stack.ctx.device_flags() == 0
     stack.close()

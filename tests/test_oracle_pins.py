@@ -224,13 +224,13 @@ def test_missing_expert_is_an_error():
 
 
 # ----------------------------------------------------------------------- stack wiring
-def _numpy_stack(x0, gates, w1, w2, k):
-    """The pre-gated wiring written out by hand with explicit indices (numpy only)."""
+def _numpy_stack(x0, gates, w1, w2, k, conventional=False):
+    """The pre-gated (or conventional) wiring written out by hand with explicit indices (numpy only)."""
     L = len(gates)
     xs = [x0]
     ys, idxs = [], []
     for i in range(L):
-        src = xs[0] if i == 0 else xs[i - 1]
+        src = xs[i] if conventional else (xs[0] if i == 0 else xs[i - 1])
         y, _, _, idx = dense_masked(src, xs[i], gates[i][0], gates[i][1], w1[i], w2[i], k)
         ys.append(y)
         idxs.append(idx)
@@ -256,6 +256,23 @@ def test_stack_wiring_matches_explicit_numpy_chain(k):
     # the wiring matters on this data: routing block i>=1 from its own input would differ
     alt = [np.argsort(-(xs[i] @ gates[i][0] + gates[i][1]), axis=1, kind="stable")[:, :k] for i in range(1, L)]
     assert any(not np.array_equal(a, idxs[i + 1]) for i, a in enumerate(alt))
+
+
+def test_conventional_wiring_matches_explicit_numpy_chain():
+    g = rng(33)
+    L, T, d, f, E, k = 3, 7, 8, 12, 4, 2
+    x0 = g.standard_normal((T, d))
+    gates = [(g.standard_normal((d, E)), None) for _ in range(L)]
+    w1 = g.standard_normal((L, E, d, f)) * 0.4
+    w2 = g.standard_normal((L, E, f, d)) * 0.4
+    out, x_last = R.stack_forward(x0, gates, k, lambda b, e: (w1[b, e], w2[b, e]), f, wiring="conventional")
+    ys, idxs, xs = _numpy_stack(x0, gates, w1, w2, k, conventional=True)
+    for i in range(L):
+        assert np.array_equal(out[i]["gate"]["idx"], idxs[i])
+        np.testing.assert_allclose(out[i]["y"], ys[i], atol=1e-11)
+    np.testing.assert_allclose(x_last, xs[-1], atol=1e-11)
+    pre, _ = R.stack_forward(x0, gates, k, lambda b, e: (w1[b, e], w2[b, e]), f)
+    assert any(not np.array_equal(pre[i]["gate"]["idx"], idxs[i]) for i in range(1, L))   # the wirings differ
 
 
 def test_pregate_reduces_to_conventional_gate_when_block_is_identity():
