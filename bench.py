@@ -99,7 +99,8 @@ def pmc_traffic(workload_name):
         return None
 
 
-def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gpu_only=True, systems=False):
+def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gpu_only=True, systems=False,
+                 cache_frac=0.2):
     import numpy as np
     import torch
 
@@ -245,6 +246,40 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
                            "note": "same workload and routing with all experts resident in HBM (no migration)"}
         stack2.close()
         del stack2, bufs2
+    if w.offloaded and cache_frac > 0:
+        # Expert cache on top of the migration (the paper's caching study: a fraction of each
+        # block's experts kept in HBM across steps; LRU here, all three policies for the headline
+        # workload).  A labelled extra: `value` above is the base design without a cache.
+        from paper_2308_12066_amd import binding as B
+        C = max(1, min(B.MAX_CACHE_SLOTS, int(np.ceil(cache_frac * E))))
+        out["expert_cache"] = {"slots_per_block": C, "fraction_of_experts": C / E}
+        pols = (("lru", B.CACHE_LRU), ("lfu", B.CACHE_LFU), ("lifo", B.CACHE_LIFO)) if systems else (("lru", B.CACHE_LRU),)
+        for pname, pol in pols:
+            stk = H.Stack(w, store, cache_slots=C, cache_policy=pol)
+            bufs = [stk.ctx.make_step_buffers(stk.gate_w, stk.gate_b, x_all[s % n_in], stk.y_blocks, idx_log[s],
+                                              stk.topk_prob, stk.row_of, stk.expert_offsets, stk.x_perm, stk.y_perm,
+                                              stk.workspace) for s in range(K)]
+            for s in range(Wm):
+                stk.ctx.stack_step(bufs[s % K], T, stk.compute, stk.copy)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for s in range(K):
+                stk.ctx.stack_step(bufs[s], T, stk.compute, stk.copy)
+            torch.cuda.synchronize()
+            dtc = time.perf_counter() - t0
+            # hit rate of a few further steps, read back step by step
+            hits = sel = 0
+            for s in range(min(K, 16)):
+                stk.ctx.stack_step(bufs[s], T, stk.compute, stk.copy)
+                torch.cuda.synchronize()
+                for b in range(L):
+                    fs = stk.ctx.fetch_stats(b)
+                    hits += fs.cache_hits
+                    sel += fs.n_unique
+            out["expert_cache"][pname] = {"tokens_per_s": T * K / dtc, "ms_per_step": 1e3 * dtc / K,
+                                          "speedup_vs_no_cache": dt / dtc, "hit_rate": hits / max(sel, 1)}
+            stk.close()
+            del stk, bufs
     if w.offloaded and systems:
         # The paper's comparison systems on the same kernels and the same workload (conventional
         # wiring): experts fetched on demand after the gate, or all experts of the next block
@@ -319,7 +354,7 @@ def main():
         others += [n for n in ("cfg4_offloaded", "cfg5", "cfg5_top2") if n not in others]
     short = {"cfg1": 8, "cfg3": 24, "cfg4": 4, "cfg4_offloaded": 2, "cfg5": 6, "cfg5_top2": 6, "base8_prefill": 4}
     keep = ("value", "unit", "steps", "ms_per_step", "ms_per_token_per_layer", "block_latency_us", "config", "roofline",
-            "host_link", "overlap", "gpu_only")
+            "host_link", "overlap", "gpu_only", "expert_cache")
     out["other_workloads"] = {}
     for n in others:
         r = run_workload(n, short.get(n, 8), 2, args.host_threads, False, None, min(args.trace_steps, 2))

@@ -76,7 +76,19 @@ typedef struct {
     int32_t slots_per_gen; /* expert slots per block generation; 0 => min(E, max_tokens*k),
                               which can never overflow.  Ignored without a host store. */
     uint32_t flags;
+    int32_t cache_slots;   /* expert cache on top of the migration (Sec. VI "Caching experts"): slots
+                              per block that keep experts in HBM across steps; 0 = no cache (the
+                              base design), at most PGMOE_MAX_CACHE_SLOTS.  Pull mode only. */
+    int32_t cache_policy;  /* pgmoe_cache_policy: which cached expert a missing one replaces */
 } pgmoe_config;
+
+/* Replacement policies the paper evaluates.  A slot whose expert is used by the current fetch
+ * is never a victim; empty slots are filled first (lowest index); ties go to the lowest slot.
+ *   LRU  victim = least recently used;
+ *   LFU  victim = least often used (then least recently used);
+ *   LIFO victim = most recently inserted. */
+typedef enum { PGMOE_CACHE_LRU = 0, PGMOE_CACHE_LFU = 1, PGMOE_CACHE_LIFO = 2 } pgmoe_cache_policy;
+#define PGMOE_MAX_CACHE_SLOTS 64
 
 /* Counters of the last pgmoe_fetch_experts() for a block (host). */
 typedef struct {
@@ -84,8 +96,9 @@ typedef struct {
     int32_t n_copied;       /* experts actually copied (== n_unique in the base design) */
     int64_t bytes_copied;   /* n_copied * expert_bytes */
     int32_t resident_slots; /* slots holding live experts over both generations right after
-                               this fetch was issued: the quantity the peak-memory rule bounds */
-    int32_t reserved;
+                               this fetch was issued: the quantity the peak-memory rule bounds
+                               (cache slots, when a cache is configured, come on top) */
+    int32_t cache_hits;     /* selected experts found in the block's cache (0 without a cache) */
     float fetch_ms;         /* copy-stream time of the batch; 0 unless pgmoe_fetch_timing() is on */
     float wait_ms;          /* host time spent waiting for the indices (memcpy mode) */
 } pgmoe_fetch_stats;
@@ -154,6 +167,10 @@ int pgmoe_register_resident_experts(pgmoe_ctx *ctx, const void *dev_base, size_t
  * If more distinct experts are selected than slots_per_gen, memcpy mode returns
  * PGMOE_ENOSLOT; pull mode copies the first slots_per_gen of them, sets device flag bit 2 and
  * the FFN skips the rows of the others (their output rows are zero).
+ * With an expert cache (cache_slots > 0) a selected expert that is still cached is not
+ * copied; a missing one replaces a victim chosen by cache_policy and is copied straight into
+ * that cache slot, or into the generation's slots when every cache slot is in use by this
+ * fetch.  The FFN then finds each expert through a per-block pointer table the fetch wrote.
  * With a resident store the call only validates and returns n_unique = -1.
  * n_unique_out host | NULL. */
 int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int T,

@@ -18,6 +18,8 @@ F32, BF16 = 0, 1
 FLAG_HOST_ONLY = 1
 FLAG_FETCH_MEMCPY = 2
 SCHED_PREGATED, SCHED_ON_DEMAND, SCHED_PREFETCH_ALL = 0, 1, 2
+CACHE_LRU, CACHE_LFU, CACHE_LIFO = 0, 1, 2
+MAX_CACHE_SLOTS = 64
 MAX_EXPERTS = 256
 
 EXPORTS = [
@@ -32,12 +34,12 @@ EXPORTS = [
 class Config(Structure):
     _fields_ = [("d_model", c_int32), ("d_ff", c_int32), ("n_experts", c_int32), ("top_k", c_int32),
                 ("n_blocks", c_int32), ("max_tokens", c_int32), ("dtype", c_int32), ("slots_per_gen", c_int32),
-                ("flags", c_uint32)]
+                ("flags", c_uint32), ("cache_slots", c_int32), ("cache_policy", c_int32)]
 
 
 class FetchStats(Structure):
     _fields_ = [("n_unique", c_int32), ("n_copied", c_int32), ("bytes_copied", c_int64),
-                ("resident_slots", c_int32), ("reserved", c_int32), ("fetch_ms", c_float), ("wait_ms", c_float)]
+                ("resident_slots", c_int32), ("cache_hits", c_int32), ("fetch_ms", c_float), ("wait_ms", c_float)]
 
 
 class BlockTrace(Structure):
@@ -125,8 +127,10 @@ def last_error(ctx=None) -> str:
     return lib.pgmoe_last_error(ctx).decode()
 
 
-def make_config(d_model, d_ff, n_experts, top_k, n_blocks, max_tokens, dtype, slots_per_gen=0, flags=0) -> Config:
-    return Config(d_model, d_ff, n_experts, top_k, n_blocks, max_tokens, dtype, slots_per_gen, flags)
+def make_config(d_model, d_ff, n_experts, top_k, n_blocks, max_tokens, dtype, slots_per_gen=0, flags=0,
+                cache_slots=0, cache_policy=0) -> Config:
+    return Config(d_model, d_ff, n_experts, top_k, n_blocks, max_tokens, dtype, slots_per_gen, flags, cache_slots,
+                  cache_policy)
 
 
 def expert_bytes(cfg: Config) -> int:

@@ -46,6 +46,11 @@ int check_config(const pgmoe_config *c, char *buf, size_t n) {
     if (c->slots_per_gen < 0 || c->slots_per_gen > c->n_experts)
         BAD("slots_per_gen=%d outside 0..n_experts", c->slots_per_gen);
     if (c->flags & ~(PGMOE_FLAG_HOST_ONLY | PGMOE_FLAG_FETCH_MEMCPY)) BAD("unknown flag bits 0x%x", c->flags);
+    if (c->cache_slots < 0 || c->cache_slots > PGMOE_MAX_CACHE_SLOTS || c->cache_slots > c->n_experts)
+        BAD("cache_slots=%d outside 0..min(%d, n_experts)", c->cache_slots, PGMOE_MAX_CACHE_SLOTS);
+    if (c->cache_policy < PGMOE_CACHE_LRU || c->cache_policy > PGMOE_CACHE_LIFO) BAD("cache_policy=%d unknown", c->cache_policy);
+    if (c->cache_slots > 0 && (c->flags & PGMOE_FLAG_FETCH_MEMCPY))
+        BAD("the expert cache is kept by the device-side pull engine: not available with PGMOE_FLAG_FETCH_MEMCPY");
     return PGMOE_OK;
 #undef BAD
 }
@@ -212,6 +217,11 @@ int pgmoe_destroy(pgmoe_ctx *c) {
     if (!c->host_only) {
         (void)hipDeviceSynchronize();
         if (c->slot_pool) (void)hipFree(c->slot_pool);
+        if (c->cache_pool) (void)hipFree(c->cache_pool);
+        if (c->cache_state) (void)hipFree(c->cache_state);
+        if (c->dev_table) (void)hipFree(c->dev_table);
+        if (c->cache_stats) (void)hipFree(c->cache_stats);
+        delete[] c->cache_parity;
         if (c->dev_flags) (void)hipFree(c->dev_flags);
         if (c->idx_staging) (void)hipHostFree(c->idx_staging);
         if (c->idx_ready) (void)hipEventDestroy(c->idx_ready);

@@ -13,6 +13,7 @@
 // of block i+1 does not queue behind that of block i: the host link stays busy across the
 // hand-over (two pull kernels share the link while they overlap).
 #include <chrono>
+#include <new>
 
 #include "pgmoe_internal.h"
 
@@ -69,6 +70,21 @@ int pgmoe_register_host_experts(pgmoe_ctx *ctx, const void *host_base, size_t ex
         if (!ctx->slot_pool) {
             const size_t bytes = (size_t)kGen * ctx->slots * ctx->expert_bytes;
             PG_HIP(ctx, hipMalloc((void **)&ctx->slot_pool, bytes));
+        }
+        if (ctx->cfg.cache_slots > 0 && !ctx->cache_pool) {
+            const size_t L = ctx->cfg.n_blocks;
+            PG_HIP(ctx, hipMalloc((void **)&ctx->cache_pool, L * ctx->cfg.cache_slots * ctx->expert_bytes));
+            PG_HIP(ctx, hipMalloc((void **)&ctx->cache_state, cache_state_bytes(ctx->cfg)));
+            PG_HIP(ctx, hipMalloc((void **)&ctx->dev_table, L * PGMOE_MAX_EXPERTS * sizeof(unsigned long long)));
+            PG_HIP(ctx, hipMalloc((void **)&ctx->cache_stats, L * 4 * sizeof(int32_t)));
+            ctx->cache_parity = new (std::nothrow) unsigned char[L]();
+            if (!ctx->cache_parity) return fail(ctx, PGMOE_EINVAL, "%s: out of host memory", fn);
+        }
+        if (ctx->cfg.cache_slots > 0) {  // (re)start with an empty cache: every slot holds expert -1
+            PG_HIP(ctx, hipDeviceSynchronize());
+            PG_HIP(ctx, hipMemset(ctx->cache_state, 0xff, cache_state_bytes(ctx->cfg)));
+            PG_HIP(ctx, hipMemset(ctx->cache_stats, 0, (size_t)ctx->cfg.n_blocks * 4 * sizeof(int32_t)));
+            memset(ctx->cache_parity, 0, (size_t)ctx->cfg.n_blocks);
         }
     }
     ctx->store_mode = STORE_HOST;
@@ -135,15 +151,18 @@ static int fetch_impl(pgmoe_ctx *ctx, const char *fn, int block, bool all, const
         if (!inline_fetch) PG_HIP(ctx, hipEventRecord(ctx->fetch_done[gen], ps));
         ctx->fetch_stream[gen] = ps;
         ctx->gen_all[gen] = all;
+        ctx->gen_table[gen] = ctx->cfg.cache_slots > 0 && !all;
         ctx->fetched_block[gen] = block;
         ctx->live_slots[gen] = -1;  // known on the device only
         st.timed = ctx->fetch_timing;
         st.pulled = true;
+        st.cached = ctx->gen_table[gen];
         st.s.n_unique = -1;
         if (n_unique_out) {
             PG_HIP(ctx, hipStreamSynchronize(ps));
             int32_t u = 0;
             PG_HIP(ctx, hipMemcpy(&u, ctx->dev_unique + block, sizeof u, hipMemcpyDeviceToHost));
+            if (ctx->gen_table[gen]) PG_HIP(ctx, hipMemcpy(&u, ctx->cache_stats + (size_t)block * 4, sizeof u, hipMemcpyDeviceToHost));
             *n_unique_out = u;
         }
         return PGMOE_OK;
@@ -190,6 +209,7 @@ static int fetch_impl(pgmoe_ctx *ctx, const char *fn, int block, bool all, const
 
     ctx->fetch_stream[gen] = ps;
     ctx->gen_all[gen] = all;
+    ctx->gen_table[gen] = false;
     ctx->fetched_block[gen] = block;
     ctx->live_slots[gen] = nu;
     st.timed = ctx->fetch_timing;
@@ -241,11 +261,19 @@ int pgmoe_get_fetch_stats(pgmoe_ctx *ctx, int block, pgmoe_fetch_stats *out) {
             PG_HIP(ctx, hipMemcpy(&u[0], ctx->dev_unique + block, sizeof(int32_t), hipMemcpyDeviceToHost));
             const bool prev_live = block > 0 && ctx->stats[block - 1].pulled;
             if (prev_live) PG_HIP(ctx, hipMemcpy(&u[1], ctx->dev_unique + block - 1, sizeof(int32_t), hipMemcpyDeviceToHost));
-            const int copied = u[0] < ctx->slots ? u[0] : ctx->slots;
+            int copied = u[0] < ctx->slots ? u[0] : ctx->slots;
             st.s.n_unique = u[0];
+            st.s.resident_slots = copied + (u[1] < ctx->slots ? u[1] : ctx->slots);
+            if (st.cached) {  // unique, copies, hits as the cache-aware kernel counted them
+                int32_t cs3[3] = {0, 0, 0};
+                PG_HIP(ctx, hipMemcpy(cs3, ctx->cache_stats + (size_t)block * 4, sizeof cs3, hipMemcpyDeviceToHost));
+                st.s.n_unique = cs3[0];
+                copied = cs3[1];
+                st.s.cache_hits = cs3[2];
+                st.s.resident_slots = cs3[0];
+            }
             st.s.n_copied = copied;
             st.s.bytes_copied = (int64_t)copied * (int64_t)ctx->expert_bytes;
-            st.s.resident_slots = copied + (u[1] < ctx->slots ? u[1] : ctx->slots);
         }
     }
     *out = st.s;
@@ -331,7 +359,8 @@ static int expert_ffn_impl(pgmoe_ctx *ctx, int block, const void *x_perm, const 
     if (ctx->trace) PG_HIP(ctx, hipEventRecord(ctx->ev_waited[block], s));
     // a generation filled by pgmoe_fetch_all_experts is indexed by expert id, else by rank
     rc = launch_ffn(ctx, ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes, ctx->expert_bytes, !ctx->gen_all[gen],
-                    ctx->slots, x_perm, expert_offsets, n_rows, y_perm, workspace, s, keep_partials);
+                    ctx->slots, x_perm, expert_offsets, n_rows, y_perm, workspace, s, keep_partials,
+                    ctx->gen_table[gen] ? ctx->dev_table + (size_t)block * PGMOE_MAX_EXPERTS : nullptr);
     if (rc) return rc;
     ctx->ffn_recorded[gen] = true;
     ctx->ffn_stream[gen] = s;

@@ -78,10 +78,174 @@ __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_kernel(
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Pull with an expert cache (the paper evaluates LIFO, LFU and LRU caches on top of the
+// migration; Sec. VI, "Caching experts").  Per block the device keeps, in two alternating
+// copies, which expert each cache slot holds and the bookkeeping the policy needs.  Every
+// workgroup reads the same (old) copy and derives the same plan in its first wavefront, one
+// lane per cache slot: selected experts that are cached are hits; each missing expert, in
+// ascending order, replaces the policy's victim among the slots not used by this fetch (empty
+// slots first) and is copied straight into that cache slot, or goes to the generation's slots
+// when no victim is left.  Workgroup 0 writes the new copy of the state, the per-expert pointer
+// table the FFN reads, and the counters.
+constexpr int CACHE_STATE_INTS = 4 * PGMOE_MAX_CACHE_SLOTS + 4;  // cexp, cuse, ccnt, cins, then tick, ins_seq
+
+__device__ inline void wave_argmin_u64(unsigned long long &key, int &lane_id) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const unsigned long long ok = __shfl_xor(key, off);
+        const int ol = __shfl_xor(lane_id, off);
+        if (ok < key || (ok == key && ol < lane_id)) {
+            key = ok;
+            lane_id = ol;
+        }
+    }
+}
+
+template <typename V>
+__global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_cache_kernel(
+    const int32_t *__restrict__ idx, int n, int E, const char *__restrict__ src_block, size_t expert_stride,
+    char *__restrict__ gen_base, size_t expert_bytes, int slots, char *__restrict__ cache_base, int C, int policy,
+    const int32_t *__restrict__ state_in, int32_t *__restrict__ state_out, unsigned long long *__restrict__ table,
+    int32_t *__restrict__ stats_out, uint32_t *flags) {
+    __shared__ int present[PGMOE_MAX_EXPERTS];               // 0 not selected, 1 selected
+    __shared__ int cp_src[PGMOE_MAX_EXPERTS];                // copies: source expert
+    __shared__ unsigned long long cp_dst[PGMOE_MAX_EXPERTS]; // copies: destination address
+    __shared__ unsigned long long tbl[PGMOE_MAX_EXPERTS];    // address of every selected expert
+    __shared__ int s_counts[4];                              // copies, unique, hits, overflow
+    const int tid = threadIdx.x, lane = tid & 63;
+    for (int e = tid; e < PGMOE_MAX_EXPERTS; e += FETCH_THREADS) {
+        present[e] = 0;
+        tbl[e] = 0ull;
+    }
+    __syncthreads();
+    bool bad = false;
+    for (int i = tid; i < n; i += FETCH_THREADS) {
+        const int e = idx[i];
+        if (e >= 0 && e < E) present[e] = 1;
+        else bad = true;
+    }
+    if (__any(bad) && lane == 0 && blockIdx.x == 0) atomicOr(flags, kFlagBadIndex);
+    __syncthreads();
+
+    if (tid < 64) {  // wavefront 0 plans; lane = cache slot
+        const bool slot = lane < C;
+        int cexp = slot ? state_in[lane] : -1;
+        int cuse = slot ? state_in[PGMOE_MAX_CACHE_SLOTS + lane] : 0;
+        int ccnt = slot ? state_in[2 * PGMOE_MAX_CACHE_SLOTS + lane] : 0;
+        int cins = slot ? state_in[3 * PGMOE_MAX_CACHE_SLOTS + lane] : 0;
+        const int tick = state_in[4 * PGMOE_MAX_CACHE_SLOTS] + 1;
+        int ins_seq = state_in[4 * PGMOE_MAX_CACHE_SLOTS + 1];
+        bool pinned = false;
+        if (slot && cexp >= 0 && present[cexp] == 1) {  // hit: distinct lanes hold distinct experts
+            pinned = true;
+            tbl[cexp] = (unsigned long long)(cache_base + (size_t)lane * expert_bytes);
+            present[cexp] = 2;
+            cuse = tick;
+            ccnt += 1;
+        }
+        const int hits = __popcll(__ballot(pinned));
+        int n_copy = 0, n_gen = 0, uniq = hits, overflow = 0;
+        for (int e = 0; e < E; ++e) {
+            if (present[e] != 1) continue;  // LDS value is uniform over the wavefront
+            ++uniq;
+            unsigned long long key = ~0ull;
+            if (slot && !pinned) {
+                if (cexp < 0) key = 0ull;  // empty slots first
+                else if (policy == PGMOE_CACHE_LRU) key = 1ull + (unsigned)cuse;
+                else if (policy == PGMOE_CACHE_LFU) key = 1ull + (((unsigned long long)(unsigned)ccnt << 32) | (unsigned)cuse);
+                else key = 1ull + (0xffffffffull - (unsigned)cins);  // LIFO: most recently inserted first
+            }
+            int v = lane;
+            wave_argmin_u64(key, v);
+            unsigned long long dst = 0ull;
+            if (key != ~0ull) {
+                if (lane == v) {
+                    cexp = e;
+                    cuse = tick;
+                    ccnt = 1;
+                    cins = ins_seq + 1;
+                    pinned = true;
+                }
+                ++ins_seq;
+                dst = (unsigned long long)(cache_base + (size_t)v * expert_bytes);
+            } else if (n_gen < slots) {
+                dst = (unsigned long long)(gen_base + (size_t)n_gen * expert_bytes);
+                ++n_gen;
+            } else {
+                overflow = 1;  // nowhere to put it: the FFN zeroes its rows (table entry stays 0)
+            }
+            if (lane == 0) {
+                tbl[e] = dst;
+                if (dst) {
+                    cp_src[n_copy] = e;
+                    cp_dst[n_copy] = dst;
+                }
+            }
+            if (dst) ++n_copy;
+        }
+        if (lane == 0) {
+            s_counts[0] = n_copy;
+            s_counts[1] = uniq;
+            s_counts[2] = hits;
+            s_counts[3] = overflow;
+        }
+        if (blockIdx.x == 0) {
+            if (slot) {
+                state_out[lane] = cexp;
+                state_out[PGMOE_MAX_CACHE_SLOTS + lane] = cuse;
+                state_out[2 * PGMOE_MAX_CACHE_SLOTS + lane] = ccnt;
+                state_out[3 * PGMOE_MAX_CACHE_SLOTS + lane] = cins;
+            }
+            if (lane == 0) {
+                state_out[4 * PGMOE_MAX_CACHE_SLOTS] = tick;
+                state_out[4 * PGMOE_MAX_CACHE_SLOTS + 1] = ins_seq;
+                stats_out[0] = uniq;
+                stats_out[1] = n_copy;
+                stats_out[2] = hits;
+                if (overflow) atomicOr(flags, kFlagNoSlot);
+            }
+        }
+    }
+    __syncthreads();
+    if (blockIdx.x == 0)
+        for (int e = tid; e < E; e += FETCH_THREADS) table[e] = tbl[e];
+
+    const unsigned upe = (unsigned)(expert_bytes / sizeof(V));
+    const unsigned total = (unsigned)s_counts[0] * upe;
+    const unsigned stride = gridDim.x * FETCH_THREADS;
+    for (unsigned i = blockIdx.x * FETCH_THREADS + tid; i < total; i += stride) {
+        const unsigned j = i / upe, of = i - j * upe;
+        reinterpret_cast<V *>(cp_dst[j])[of] =
+            __builtin_nontemporal_load(reinterpret_cast<const V *>(src_block + (size_t)cp_src[j] * expert_stride) + of);
+    }
+}
+
+size_t cache_state_bytes(const pgmoe_config &c) { return (size_t)c.n_blocks * 2 * CACHE_STATE_INTS * sizeof(int32_t); }
+
 int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, int n, hipStream_t s) {
     const int gen = block & 1;
     char *gen_base = ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes;
     const char *src = ctx->store_dev + (size_t)block * ctx->block_stride;
+    if (ctx->cfg.cache_slots > 0 && !all) {
+        const int C = ctx->cfg.cache_slots, par = ctx->cache_parity[block];
+        char *cache_base = ctx->cache_pool + (size_t)block * C * ctx->expert_bytes;
+        const int32_t *st_in = ctx->cache_state + ((size_t)block * 2 + par) * CACHE_STATE_INTS;
+        int32_t *st_out = ctx->cache_state + ((size_t)block * 2 + (par ^ 1)) * CACHE_STATE_INTS;
+        unsigned long long *table = ctx->dev_table + (size_t)block * PGMOE_MAX_EXPERTS;
+        int32_t *stats = ctx->cache_stats + (size_t)block * 4;
+        if (ctx->expert_bytes % 16 == 0)
+            hipLaunchKernelGGL(fetch_pull_cache_kernel<u32x4>, dim3(FETCH_GRID), dim3(FETCH_THREADS), 0, s, idx, n,
+                               ctx->cfg.n_experts, src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, cache_base,
+                               C, ctx->cfg.cache_policy, st_in, st_out, table, stats, ctx->dev_flags);
+        else
+            hipLaunchKernelGGL(fetch_pull_cache_kernel<unsigned int>, dim3(FETCH_GRID), dim3(FETCH_THREADS), 0, s, idx, n,
+                               ctx->cfg.n_experts, src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, cache_base,
+                               C, ctx->cfg.cache_policy, st_in, st_out, table, stats, ctx->dev_flags);
+        PG_HIP(ctx, hipGetLastError());
+        ctx->cache_parity[block] = par ^ 1;
+        return PGMOE_OK;
+    }
     if (ctx->expert_bytes % 16 == 0)
         hipLaunchKernelGGL(fetch_pull_kernel<u32x4>, dim3(FETCH_GRID), dim3(FETCH_THREADS), 0, s, idx, n, ctx->cfg.n_experts,
                            src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, all ? 1 : 0, ctx->dev_unique + block,

@@ -99,8 +99,8 @@ __device__ inline void lds_barrier() {
 template <int MT, int KT, int NW, int D>
 __global__ __launch_bounds__(NW * 64) void ffn_fused_kernel(
     const __bf16 *__restrict__ x_perm, const int32_t *__restrict__ offsets, int E, int f, int f_range,
-    const char *__restrict__ w_base, size_t w_stride, int slot_by_rank, int n_slots, float *__restrict__ partial,
-    __bf16 *__restrict__ y_perm, int n_rows) {
+    const char *__restrict__ w_base, size_t w_stride, int slot_by_rank, int n_slots,
+    const unsigned long long *__restrict__ table, float *__restrict__ partial, __bf16 *__restrict__ y_perm, int n_rows) {
     constexpr int SUB = 16 * NW;      // d_ff columns per sub-slab
     constexpr int KTB = SUB / 32;     // k-tiles of phase B per sub-slab
     constexpr int NTD = KT * 2;       // n-tiles of the output (d_model / 16)
@@ -114,9 +114,11 @@ __global__ __launch_bounds__(NW * 64) void ffn_fused_kernel(
 
     const ChunkInfo ci = find_chunk(offsets, E, 16 * MT, blockIdx.x);
     if (ci.nrows == 0) return;  // uniform over the workgroup
-    const bool no_weights = slot_by_rank && ci.slot >= n_slots;  // expert did not get a slot: rows are zeroed
+    // where the expert's blob is: through the cache's pointer table, by slot rank, or by expert id
+    const char *wexp = table ? reinterpret_cast<const char *>(table[ci.expert])
+                             : w_base + (size_t)(slot_by_rank ? ci.slot : ci.expert) * w_stride;
+    const bool no_weights = table ? wexp == nullptr : (slot_by_rank && ci.slot >= n_slots);  // no slot: rows are zeroed
 
-    const char *wexp = w_base + (size_t)(slot_by_rank ? ci.slot : ci.expert) * w_stride;
     const bf16x8 *w1 = reinterpret_cast<const bf16x8 *>(wexp) + lane;
     const bf16x8 *w2 = reinterpret_cast<const bf16x8 *>(wexp + (size_t)d * f * 2) + lane;
     const int n_sub = no_weights ? 0 : f_range / SUB;
@@ -291,15 +293,18 @@ __device__ inline void find_row_expert(const int32_t *offsets, int E, int row, i
 __global__ __launch_bounds__(256) void ffn_f32_hidden_kernel(const float *__restrict__ x_perm,
                                                               const int32_t *__restrict__ offsets, int E, int d, int f,
                                                               const char *__restrict__ w_base, size_t w_stride,
-                                                              int slot_by_rank, int n_slots, float *__restrict__ h) {
+                                                              int slot_by_rank, int n_slots,
+                                                              const unsigned long long *__restrict__ table,
+                                                              float *__restrict__ h) {
     __shared__ int s_e, s_s;
     const int row = blockIdx.x;
     if (threadIdx.x == 0) find_row_expert(offsets, E, row, &s_e, &s_s);
     __syncthreads();
-    const float *w1 = reinterpret_cast<const float *>(w_base + (size_t)(slot_by_rank ? s_s : s_e) * w_stride);
+    const float *w1 = table ? reinterpret_cast<const float *>(table[s_e])
+                            : reinterpret_cast<const float *>(w_base + (size_t)(slot_by_rank ? s_s : s_e) * w_stride);
     const int j = blockIdx.y * 256 + threadIdx.x;
     if (j >= f) return;
-    if (slot_by_rank && s_s >= n_slots) {  // expert did not get a slot
+    if (table ? w1 == nullptr : (slot_by_rank && s_s >= n_slots)) {  // expert did not get a slot
         h[(size_t)row * f + j] = 0.f;
         return;
     }
@@ -312,15 +317,18 @@ __global__ __launch_bounds__(256) void ffn_f32_hidden_kernel(const float *__rest
 __global__ __launch_bounds__(256) void ffn_f32_out_kernel(const float *__restrict__ h, const int32_t *__restrict__ offsets,
                                                            int E, int d, int f, const char *__restrict__ w_base,
                                                            size_t w_stride, int slot_by_rank, int n_slots,
+                                                           const unsigned long long *__restrict__ table,
                                                            float *__restrict__ y_perm) {
     __shared__ int s_e, s_s;
     const int row = blockIdx.x;
     if (threadIdx.x == 0) find_row_expert(offsets, E, row, &s_e, &s_s);
     __syncthreads();
-    const float *w2 = reinterpret_cast<const float *>(w_base + (size_t)(slot_by_rank ? s_s : s_e) * w_stride) + (size_t)d * f;
+    const float *wb = table ? reinterpret_cast<const float *>(table[s_e])
+                            : reinterpret_cast<const float *>(w_base + (size_t)(slot_by_rank ? s_s : s_e) * w_stride);
+    const float *w2 = wb + (size_t)d * f;
     const int c = blockIdx.y * 256 + threadIdx.x;
     if (c >= d) return;
-    if (slot_by_rank && s_s >= n_slots) {
+    if (table ? wb == nullptr : (slot_by_rank && s_s >= n_slots)) {
         y_perm[(size_t)row * d + c] = 0.f;
         return;
     }
@@ -395,7 +403,7 @@ static int timing_slot(pgmoe_ctx *ctx) {
 template <int MT, int KT, int NW, int D>
 static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots,
                         const void *x_perm, const int32_t *offsets, int n_rows, void *y_perm, void *workspace,
-                        hipStream_t s, int *keep_partials) {
+                        hipStream_t s, int *keep_partials, const unsigned long long *table) {
     const pgmoe_config &c = ctx->cfg;
     const size_t lds = (size_t)MT * KT * 1024 + 2u * MT * (16 * NW / 32) * 1024;
     auto kern = ffn_fused_kernel<MT, KT, NW, D>;
@@ -410,7 +418,7 @@ static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, si
     const int tslot = timing_slot(ctx);
     if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_begin[tslot], s));
     hipLaunchKernelGGL(kern, dim3(p.max_chunks, p.n_partial), dim3(NW * 64), lds, s, (const __bf16 *)x_perm, offsets,
-                       c.n_experts, c.d_ff, p.f_range, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, partial, (__bf16 *)y_perm,
+                       c.n_experts, c.d_ff, p.f_range, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, partial, (__bf16 *)y_perm,
                        n_rows);
     PG_HIP(ctx, hipGetLastError());
     if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
@@ -436,7 +444,8 @@ static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, si
 }
 
 int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots, const void *x_perm,
-               const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s, int *keep_partials) {
+               const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s, int *keep_partials,
+               const unsigned long long *table) {
     const pgmoe_config &c = ctx->cfg;
     if (keep_partials) *keep_partials = 0;
     if (n_rows == 0) return PGMOE_OK;
@@ -446,10 +455,10 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
         if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_begin[tslot], s));
         hipLaunchKernelGGL(ffn_f32_hidden_kernel, dim3(n_rows, (c.d_ff + 255) / 256), dim3(256), 0, s,
                            (const float *)x_perm, offsets, c.n_experts, c.d_model, c.d_ff, w_base, w_stride,
-                           slot_by_rank ? 1 : 0, n_slots, h);
+                           slot_by_rank ? 1 : 0, n_slots, table, h);
         PG_HIP(ctx, hipGetLastError());
         hipLaunchKernelGGL(ffn_f32_out_kernel, dim3(n_rows, (c.d_model + 255) / 256), dim3(256), 0, s, h, offsets,
-                           c.n_experts, c.d_model, c.d_ff, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, (float *)y_perm);
+                           c.n_experts, c.d_model, c.d_ff, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, (float *)y_perm);
         PG_HIP(ctx, hipGetLastError());
         if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
         return PGMOE_OK;
@@ -458,7 +467,7 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
     const int kt = c.d_model / 32;
     if (c.d_ff % (16 * p.nw)) return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: d_ff=%d is not a multiple of the %d-column sub-slab", c.d_ff, 16 * p.nw);
 #define PG_CASE(MT_, KT_, NW_, D_) \
-    if (p.mt == MT_ && kt == KT_ && p.nw == NW_) return launch_fused<MT_, KT_, NW_, D_>(ctx, p, w_base, w_stride, slot_by_rank, n_slots, x_perm, offsets, n_rows, y_perm, workspace, s, keep_partials)
+    if (p.mt == MT_ && kt == KT_ && p.nw == NW_) return launch_fused<MT_, KT_, NW_, D_>(ctx, p, w_base, w_stride, slot_by_rank, n_slots, x_perm, offsets, n_rows, y_perm, workspace, s, keep_partials, table)
     PG_CASE(1, 2, 4, 4); PG_CASE(1, 4, 4, 8); PG_CASE(1, 8, 4, 16); PG_CASE(1, 16, 4, 16); PG_CASE(1, 24, 4, 16);
     PG_CASE(1, 32, 4, 16); PG_CASE(1, 64, 4, 16); PG_CASE(1, 24, 2, 24); PG_CASE(1, 32, 2, 24);
     PG_CASE(2, 2, 4, 4); PG_CASE(2, 4, 4, 8); PG_CASE(2, 8, 4, 16); PG_CASE(2, 16, 4, 16); PG_CASE(2, 24, 4, 16);

@@ -28,6 +28,7 @@ struct BlockStats {
     pgmoe_fetch_stats s;
     bool timed;   // fetch_begin/fetch_end were recorded for this block
     bool pulled;  // fetched by the pull kernel: counts live on the device
+    bool cached;  // ... through the expert cache: counts in cache_stats
 };
 
 }  // namespace pgmoe
@@ -64,6 +65,14 @@ struct pgmoe_ctx {
     hipStream_t fetch_stream[pgmoe::kGen];  // stream the generation's last fetch ran on
     hipStream_t copy2;                      // internal second copy stream
     bool gen_all[pgmoe::kGen];              // generation holds every expert of its block (slot = expert id)
+    bool gen_table[pgmoe::kGen];            // generation was filled through the expert cache: FFN reads dev_table
+
+    // expert cache (cfg.cache_slots > 0)
+    char *cache_pool;                 // [n_blocks][cache_slots][expert_bytes]
+    int32_t *cache_state;             // [n_blocks][2][state] device
+    unsigned long long *dev_table;    // [n_blocks][PGMOE_MAX_EXPERTS] device address of every selected expert
+    int32_t *cache_stats;             // [n_blocks][4] device: unique, copies, hits
+    unsigned char *cache_parity;      // [n_blocks] host: which state copy is current
     int schedule;                           // PGMOE_SCHED_*
     bool fetch_timing;               // record fetch_begin / fetch_end
     bool trace;                      // record the per-block compute-stream events below
@@ -115,7 +124,8 @@ int launch_permute(pgmoe_ctx *ctx, const void *x, const int32_t *idx, int T, voi
 // keep_partials != nullptr: if the launch produces float32 partial sums, leave them in the
 // workspace unreduced and report their number there (0 = y_perm was written directly).
 int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots, const void *x_perm,
-               const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s, int *keep_partials = nullptr);
+               const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s, int *keep_partials = nullptr,
+               const unsigned long long *table = nullptr);  // table: per-expert weight addresses (0 = none), overrides w_base
 // p-lanes of the partial-sum reduction for P partials (fixes the order of the additions)
 inline int reduce_lanes(int P) { return P <= 2 ? 1 : (P <= 8 ? 4 : 16); }
 // Combine straight from P unreduced float32 partials [P][n_rows][d] (bf16 contexts only): same
@@ -123,6 +133,7 @@ inline int reduce_lanes(int P) { return P <= 2 ? 1 : (P <= 8 ? 4 : 16); }
 int launch_combine_partials(pgmoe_ctx *ctx, const float *partial, int P, int n_rows, const int32_t *row_of,
                             const float *prob, int T, void *y, const void *x_res, void *x_next, hipStream_t s);
 int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, int n, hipStream_t s);
+size_t cache_state_bytes(const pgmoe_config &c);
 int launch_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, const float *prob, int T,
                    void *y, const void *x_res, void *x_next, hipStream_t s);
 

@@ -522,3 +522,42 @@ def test_comparison_schedules_match_the_conventional_oracle(hx, schedule, fetch,
                 assert fs.n_copied == expect and fs.bytes_copied == expect * w.expert_bytes
     assert stack.ctx.device_flags() == 0
     stack.close()
+
+
+# ------------------------------------------------------------------------------ expert cache
+@pytest.mark.parametrize("policy", ["lru", "lfu", "lifo"])
+def test_expert_cache_changes_the_copies_not_the_results(hx, policy):
+    """A stack with an expert cache gives bit-identical hidden states to the same stack without
+    one, and the device's hit / copy counts equal the reference model of the policy."""
+    from oracle.cache_policy import ExpertCache, LRU, LFU, LIFO
+    H, B = hx
+    pol = {"lru": (B.CACHE_LRU, LRU), "lfu": (B.CACHE_LFU, LFU), "lifo": (B.CACHE_LIFO, LIFO)}[policy]
+    w = W.Workload("cache_case", 95, 4, 256, 512, 32, 2, 12, 1, "bf16", 1.1, True)
+    C = 6
+    cfg = H.config_for(w)
+    store = H.ExpertStore(w, cfg, threads=4)
+    gates = W.gate_tensors(w)
+    plain = H.Stack(w, store, gates=gates)
+    cached = H.Stack(w, store, gates=gates, cache_slots=C, cache_policy=pol[0])
+    models = [ExpertCache(C, pol[1]) for _ in range(w.n_blocks)]
+    hits_total = 0
+    for s in range(10):
+        x0 = W.step_input(w, s)
+        for st in (plain, cached):
+            st.set_input(x0)
+            st.step()
+        torch.cuda.synchronize()
+        assert torch.equal(plain.x_states, cached.x_states), f"step {s}: the cache changed the hidden states"
+        assert torch.equal(plain.topk_idx, cached.topk_idx)
+        for b in range(w.n_blocks):
+            ref = models[b].fetch(np.unique(cached.topk_idx[b].cpu().numpy()))
+            fs = cached.ctx.fetch_stats(b)
+            assert (fs.n_unique, fs.cache_hits, fs.n_copied) == (ref["unique"], ref["hits"], len(ref["copies"])), \
+                f"step {s} block {b}: device {(fs.n_unique, fs.cache_hits, fs.n_copied)} vs model {ref}"
+            assert fs.bytes_copied == len(ref["copies"]) * w.expert_bytes
+            hits_total += fs.cache_hits
+    say(f"  cache {policy}: {hits_total} hits over 10 steps x {w.n_blocks} blocks")
+    assert hits_total > 0
+    assert cached.ctx.device_flags() == 0
+    plain.close()
+    cached.close()

@@ -299,3 +299,34 @@ def test_fetch_set_is_the_unique_selected_experts():
     r = R.route(idx, 64)
     assert np.array_equal(r["unique"], np.unique(idx))
     assert len(r["unique"]) <= 16
+
+
+# ----------------------------------------------------------------------- cache policy model
+def test_cache_policy_model_on_hand_traced_sequences():
+    """The reference model of the expert cache against sequences traced by hand."""
+    from oracle.cache_policy import ExpertCache, LRU, LFU, LIFO
+    # LRU, 2 slots: 1,2 fill; 1 hits; 3 evicts 2 (1 was used later); 2 evicts 1? no: 3 then 2 -> victim is 1
+    c = ExpertCache(2, LRU)
+    assert c.fetch([1])["copies"] == [(1, "cache", 0)]
+    assert c.fetch([2])["copies"] == [(2, "cache", 1)]
+    r = c.fetch([1]); assert r["hits"] == 1 and r["copies"] == []
+    assert c.fetch([3])["copies"] == [(3, "cache", 1)]          # 2 is least recently used
+    assert c.fetch([2])["copies"] == [(2, "cache", 0)]          # now 1 is
+    # LFU, 2 slots: 1 used three times, 2 once -> 3 evicts 2; then 4 evicts 3 (count 1, older than nothing else)
+    c = ExpertCache(2, LFU)
+    c.fetch([1]); c.fetch([1]); c.fetch([1]); c.fetch([2])
+    assert c.fetch([3])["copies"] == [(3, "cache", 1)]
+    assert c.fetch([4])["copies"] == [(4, "cache", 1)]
+    assert c.fetch([1])["hits"] == 1
+    # LIFO, 3 slots: 5,6,7 fill in order; 8 evicts 7 (last in); 9 evicts 8
+    c = ExpertCache(3, LIFO)
+    assert [x[2] for x in c.fetch([5, 6, 7])["copies"]] == [0, 1, 2]
+    assert c.fetch([8])["copies"] == [(8, "cache", 2)]
+    assert c.fetch([9])["copies"] == [(9, "cache", 2)]
+    assert c.fetch([5, 6])["hits"] == 2
+    # a fetch never evicts what it uses itself; what does not fit goes to the ordinary slots
+    c = ExpertCache(2, LRU)
+    r = c.fetch([4, 1, 3])
+    assert r["copies"] == [(1, "cache", 0), (3, "cache", 1), (4, "gen", 0)] and r["unique"] == 3
+    r = c.fetch([1, 2, 3])
+    assert r["hits"] == 2 and r["copies"] == [(2, "gen", 0)]
