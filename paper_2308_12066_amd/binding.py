@@ -62,6 +62,14 @@ class PgmoeError(RuntimeError):
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2308_12066_amd.build`")
+    # One HIP runtime per process: torch ships its own libamdhip64 and looks it up under a
+    # different file name than the system one, so if this library came first the process would
+    # hold two runtimes and the second to start would see no device.  Loading torch first makes
+    # libpgmoe bind to the runtime torch already brought in (same soname).
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = ctypes.CDLL(LIB_PATH)
     vp, i = c_void_p, c_int
     L.pgmoe_create.argtypes = [POINTER(vp), POINTER(Config)]

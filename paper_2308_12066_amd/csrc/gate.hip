@@ -8,6 +8,8 @@
 // per token does the softmax and k rounds of arg-max with shuffles.  Two kernels: a vectorised
 // one for power-of-two expert counts (every configuration of the paper) and a scalar one for
 // any other E.
+#include <cstdlib>
+
 #include "pgmoe_internal.h"
 
 namespace pgmoe {
@@ -19,12 +21,12 @@ constexpr int GATE_THREADS = 256;
 __device__ inline float to_float(float v) { return v; }
 __device__ inline float to_float(__bf16 v) { return (float)v; }
 
-// (value, index) arg-max over the wavefront; equal values keep the lower index.
-__device__ inline void wave_argmax(float &v, int &i) {
+// (value, index) arg-max over a group of 16 lanes; equal values keep the lower index.
+__device__ inline void group_argmax(float &v, int &i) {
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const float ov = __shfl_xor(v, off);
-        const int oi = __shfl_xor(i, off);
+    for (int off = 8; off >= 1; off >>= 1) {
+        const float ov = __shfl_xor(v, off, 16);
+        const int oi = __shfl_xor(i, off, 16);
         if (ov > v || (ov == v && oi < i)) {
             v = ov;
             i = oi;
@@ -33,69 +35,72 @@ __device__ inline void wave_argmax(float &v, int &i) {
 }
 
 // Softmax over the E logits of each token and k rounds of arg-max (ties to the lowest index,
-// NaN ranks as -infinity and raises the NaN flag).  zs: LDS [tokens][PGMOE_MAX_EXPERTS] logits.
-// One wavefront per token; a lane holds experts lane, lane+64, lane+128, lane+192.
-__device__ inline void softmax_topk(const float *zs, int t0, int nt, int E, int k, int32_t *__restrict__ idx_out,
-                                    float *__restrict__ prob_out, float *__restrict__ probs_out, uint32_t *flags) {
+// NaN ranks as -infinity and raises the NaN flag).  zs: LDS [tokens][zstride] logits.
+// Sixteen lanes per token, so a wavefront works on four tokens at once; lane s of a group holds
+// experts s, s+16, s+32, ... (at most 16 of them, E <= 256).
+__device__ inline void softmax_topk(const float *zs, int zstride, int t0, int nt, int E, int k,
+                                    int32_t *__restrict__ idx_out, float *__restrict__ prob_out,
+                                    float *__restrict__ probs_out, uint32_t *flags) {
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    for (int t = wave; t < nt; t += GATE_THREADS / 64) {
-        float v[4];
-        bool saw_nan = false;
+    const int sub = tid & 15, grp = tid >> 4;  // 16 groups per 256-thread workgroup
+    bool any_nan = false;
+    for (int tb = 0; tb < nt; tb += GATE_THREADS / 16) {  // uniform trip count; idle groups just skip the writes
+        const int t = tb + grp;
+        const bool live = t < nt;
+        float v[16];
         float m = -INFINITY;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int ee = lane + 64 * q;
-            float z = ee < E ? zs[t * PGMOE_MAX_EXPERTS + ee] : -INFINITY;
+        for (int q = 0; q < 16; ++q) {
+            const int ee = sub + 16 * q;
+            float z = (live && ee < E) ? zs[t * zstride + ee] : -INFINITY;
             if (z != z) {
                 z = -INFINITY;
-                saw_nan = true;
+                any_nan = true;
             }
             v[q] = z;
             m = fmaxf(m, z);
         }
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-        float p[4], s = 0.f;
+        for (int off = 8; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 16));
+        float p[16], s = 0.f;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            p[q] = (lane + 64 * q < E) ? expf(v[q] - m) : 0.f;
+        for (int q = 0; q < 16; ++q) {
+            p[q] = (sub + 16 * q < E) ? expf(v[q] - m) : 0.f;
             s += p[q];
         }
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+        for (int off = 8; off >= 1; off >>= 1) s += __shfl_xor(s, off, 16);
         const float inv = 1.f / s;
         const size_t tok = (size_t)(t0 + t);
-        if (probs_out) {
+        if (probs_out && live) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (lane + 64 * q < E) probs_out[tok * E + lane + 64 * q] = p[q] * inv;
+            for (int q = 0; q < 16; ++q)
+                if (sub + 16 * q < E) probs_out[tok * E + sub + 16 * q] = p[q] * inv;
         }
-        if (__any(saw_nan) && lane == 0) atomicOr(flags, kFlagNaN);
-
         unsigned taken = 0;
         for (int j = 0; j < k; ++j) {
             float bv = -INFINITY;
             int bi = 0x7fffffff;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int ee = lane + 64 * q;
+            for (int q = 0; q < 16; ++q) {
+                const int ee = sub + 16 * q;
                 // strict > keeps the lowest index of this lane; untaken -inf entries still compete by index
                 if (ee < E && !(taken >> q & 1) && (bi == 0x7fffffff || v[q] > bv)) {
                     bv = v[q];
                     bi = ee;
                 }
             }
-            wave_argmax(bv, bi);
+            group_argmax(bv, bi);
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (lane + 64 * q == bi) taken |= 1u << q;
-            if (lane == 0) {
+            for (int q = 0; q < 16; ++q)
+                if (sub + 16 * q == bi) taken |= 1u << q;
+            if (sub == 0 && live) {
                 idx_out[tok * k + j] = bi;
                 prob_out[tok * k + j] = expf(bv - m) * inv;
             }
         }
     }
+    if (__any(any_nan) && (tid & 63) == 0) atomicOr(flags, kFlagNaN);
 }
 
 template <typename XT>
@@ -146,7 +151,7 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_kernel(
     }
     __syncthreads();
 
-    softmax_topk(zs, t0, nt, E, k, idx_out, prob_out, probs_out, flags);
+    softmax_topk(zs, PGMOE_MAX_EXPERTS, t0, nt, E, k, idx_out, prob_out, probs_out, flags);
 }
 
 // Fast path for E in {8, 16, 32, 64, 128, 256}: thread (rg, cv) owns the 8 experts 8*cv..8*cv+7
@@ -218,7 +223,91 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_vec_kernel(
         zs[t * PGMOE_MAX_EXPERTS + e] = sum + (bias ? bias[e] : 0.f);
     }
     __syncthreads();
-    softmax_topk(zs, t0, nt, E, k, idx_out, prob_out, probs_out, flags);
+    softmax_topk(zs, PGMOE_MAX_EXPERTS, t0, nt, E, k, idx_out, prob_out, probs_out, flags);
+}
+
+// Matrix-core path (bf16, E a multiple of 8, d_model a multiple of 32): the gate is a skinny
+// GEMM [T,d] x [d,E].  A workgroup takes 16 tokens (one matrix-core tile); its four wavefronts
+// split the d_model reduction (k-tile kt goes to wavefront kt % 4) and their partial logits are
+// added in LDS in wavefront order.  Nothing is staged through LDS on the way in:
+//   * the token operand (16 tokens x 32 k) is one 16-byte load per lane straight from x;
+//   * W is row-major [d,E], an expert's weights are strided, but lane (n, g) can load rows
+//     32*kt + 8*g .. +7 of the eight experts 8*n .. 8*n+7 with eight contiguous 16-byte loads and
+//     transpose the 8x8 block in registers.  Product q (q = 0..7) then takes from every lane the
+//     eight k-values of expert 8*n + q: that is a valid operand for the 16 experts
+//     {q, 8+q, 16+q, ...}, i.e. output column n of product q is expert 8*n + q.  Eight products
+//     cover 128 experts per k-tile; E = 256 takes a second pass.
+typedef __bf16 gbf16x8 __attribute__((ext_vector_type(8)));
+typedef float gfloatx4 __attribute__((ext_vector_type(4)));
+constexpr int GM_TOK = 16;  // tokens per workgroup
+
+template <int NP>  // passes of 128 experts (1: E <= 128, 2: E <= 256)
+__global__ __launch_bounds__(GATE_THREADS) void gate_topk_mfma_kernel(
+    const __bf16 *__restrict__ x, const __bf16 *__restrict__ w, const float *__restrict__ bias, int T, int d, int E, int k,
+    int32_t *__restrict__ idx_out, float *__restrict__ prob_out, float *__restrict__ probs_out, uint32_t *flags) {
+    extern __shared__ __attribute__((aligned(16))) char gsm[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, g = lane >> 4;
+    const int t0 = blockIdx.x * GM_TOK;
+    const int nt = min(GM_TOK, T - t0);
+    const int KT = d >> 5;
+    const int ncv = E >> 3;           // 8-expert column vectors per W row
+    const int ecols = NP * 128;       // logit columns kept per token in LDS
+    float *part = reinterpret_cast<float *>(gsm);            // [4][GM_TOK][ecols]
+    float *zs = part + 4 * GM_TOK * ecols;                   // [GM_TOK][ecols]
+
+    gfloatx4 acc[NP][8];
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[p][q] = gfloatx4{0.f, 0.f, 0.f, 0.f};
+
+    const bool tok_ok = n < nt;
+    const __bf16 *xrow = x + (size_t)(t0 + (tok_ok ? n : 0)) * d + 8 * g;
+    for (int kt = wave; kt < KT; kt += 4) {
+        gbf16x8 a = *reinterpret_cast<const gbf16x8 *>(xrow + kt * 32);
+        if (!tok_ok) a = gbf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int cv = n + 16 * p;
+            gbf16x8 rows[8];
+            if (cv < ncv) {
+                const gbf16x8 *src = reinterpret_cast<const gbf16x8 *>(w + (size_t)(kt * 32 + 8 * g) * E) + cv;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) rows[j] = src[(size_t)j * ncv];
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) rows[j] = gbf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                gbf16x8 cell;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) cell[j] = rows[j][q];
+                acc[p][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, cell, acc[p][q], 0, 0, 0);
+            }
+        }
+    }
+    // lane holds tokens 4*g + r (r = 0..3), column n of product q = expert 8*(n + 16*p) + q
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int e = 8 * (n + 16 * p) + q;
+            float *dst = part + ((size_t)wave * GM_TOK + 4 * g) * ecols + e;
+            dst[0 * ecols] = acc[p][q].x;
+            dst[1 * ecols] = acc[p][q].y;
+            dst[2 * ecols] = acc[p][q].z;
+            dst[3 * ecols] = acc[p][q].w;
+        }
+    __syncthreads();
+    for (int o = tid; o < GM_TOK * ecols; o += GATE_THREADS) {
+        const int e = o % ecols;
+        const float sum = ((part[o] + part[GM_TOK * ecols + o]) + part[2 * GM_TOK * ecols + o]) + part[3 * GM_TOK * ecols + o];
+        zs[o] = sum + ((bias && e < E) ? bias[e] : 0.f);
+    }
+    __syncthreads();
+    softmax_topk(zs, ecols, t0, nt, E, k, idx_out, prob_out, probs_out, flags);
 }
 
 template <typename XT>
@@ -242,9 +331,34 @@ static void launch_gate_t(const pgmoe_config &c, const XT *x, const XT *w, const
 #undef PG_GATE
 }
 
+static int launch_gate_mfma(pgmoe_ctx *ctx, const __bf16 *x, const __bf16 *w, const float *bias, int T, int32_t *idx,
+                            float *prob, float *probs, hipStream_t s) {
+    const pgmoe_config &c = ctx->cfg;
+    const int np = c.n_experts <= 128 ? 1 : 2;
+    const size_t lds = (size_t)5 * GM_TOK * np * 128 * sizeof(float);  // 4 partial planes + the logits
+    const dim3 grid((T + GM_TOK - 1) / GM_TOK);
+    if (np == 1) {
+        hipLaunchKernelGGL(gate_topk_mfma_kernel<1>, grid, dim3(GATE_THREADS), lds, s, x, w, bias, T, c.d_model, c.n_experts,
+                           c.top_k, idx, prob, probs, ctx->dev_flags);
+    } else {
+        auto kern = gate_topk_mfma_kernel<2>;
+        static thread_local bool attr_set = false;
+        if (!attr_set) {
+            PG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(kern, grid, dim3(GATE_THREADS), lds, s, x, w, bias, T, c.d_model, c.n_experts, c.top_k, idx, prob,
+                           probs, ctx->dev_flags);
+    }
+    PG_HIP(ctx, hipGetLastError());
+    return PGMOE_OK;
+}
+
 int launch_gate(pgmoe_ctx *ctx, const void *x, const void *w, const float *bias, int T, int32_t *idx,
                 float *prob, float *probs, hipStream_t s) {
     const pgmoe_config &c = ctx->cfg;
+    if (c.dtype == PGMOE_BF16 && c.n_experts % 8 == 0 && c.d_model % 32 == 0 && !getenv("PGMOE_GATE_NO_MFMA"))
+        return launch_gate_mfma(ctx, (const __bf16 *)x, (const __bf16 *)w, bias, T, idx, prob, probs, s);
     if (c.dtype == PGMOE_F32)
         launch_gate_t<float>(c, (const float *)x, (const float *)w, bias, T, idx, prob, probs, ctx->dev_flags, s);
     else
