@@ -100,7 +100,7 @@ def pmc_traffic(workload_name):
 
 
 def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gpu_only=True, systems=False,
-                 cache_frac=0.2):
+                 cache_frac=0.2, store=None):
     import numpy as np
     import torch
 
@@ -114,7 +114,9 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
 
     t0 = time.perf_counter()
     cfg = H.config_for(w)
-    store = H.ExpertStore(w, cfg, threads=host_threads)
+    own_store = store is None
+    if own_store:
+        store = H.ExpertStore(w, cfg, threads=host_threads)
     stack = H.Stack(w, store)
     # Every timed step gets its own hidden-state block (slice 0 pre-filled with that step's
     # input) and its own routing-index slice, so the timed loop holds library calls only.
@@ -327,6 +329,29 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
     return out
 
 
+def activated_expert_sweep(host_threads, steps):
+    """Block latency of the four systems against the number of activated experts on the
+    Switch-Base-64 shape at batch 1 (the paper's micro-benchmark, Sec. VI-D), each normalised to
+    GPU-only at the same k.  One expert store serves every k (same seed index)."""
+    import workloads as W
+    from paper_2308_12066_amd import harness as H
+
+    first = W.CONFIGS[f"sweep64_k{W.SWEEP_K[0]}"]
+    store = H.ExpertStore(first, H.config_for(first), threads=host_threads)
+    rows = {}
+    for k in W.SWEEP_K:
+        r = run_workload(f"sweep64_k{k}", steps, 2, host_threads, False, None, 0, systems=True, cache_frac=0.0, store=store)
+        sysm = r["systems"]
+        g = sysm["gpu_only"]["block_latency_us"]
+        rows[str(k)] = {n: {"block_latency_us": v["block_latency_us"], "vs_gpu_only": v["block_latency_us"] / g,
+                            "peak_resident_expert_MB": v["peak_resident_expert_MB"]} for n, v in sysm.items()}
+        rows[str(k)]["link_GBps"] = r["host_link"]["achieved_GBps"]
+        log(f"[bench] sweep k={k}: " + ", ".join(f"{n} {v['block_latency_us']:.0f} us" for n, v in sysm.items()))
+    del store
+    return {"shape": "Switch-Base-64 (d_model 768, d_ff 3072, 64 experts, 6 blocks), 1 token per step",
+            "steps": steps, "by_top_k": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -339,6 +364,8 @@ def main():
     ap.add_argument("--cpu-sample-steps", type=int, default=None)
     ap.add_argument("--trace-steps", type=int, default=8)
     ap.add_argument("--host-threads", type=int, default=16)
+    ap.add_argument("--sweep-k", action="store_true",
+                    help="add the activated-expert sweep (top-1..64 on the Switch-Base-64 shape, four systems)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -359,6 +386,8 @@ def main():
     for n in others:
         r = run_workload(n, short.get(n, 8), 2, args.host_threads, False, None, min(args.trace_steps, 2))
         out["other_workloads"][n] = {k: r[k] for k in keep if k in r}
+    if args.sweep_k:
+        out["activated_expert_sweep"] = activated_expert_sweep(args.host_threads, 16)
     print(json.dumps(out), flush=True)
 
 

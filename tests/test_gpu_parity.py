@@ -343,6 +343,7 @@ def test_cfg1_tiny_f32_stack_all_tokens(hx):
     ("cfg2", 6, 6, None, "pull"), ("cfg2", 6, 4, None, "memcpy"), ("cfg3", 6, 3, None, "pull"),
     ("cfg4", 2, 1, 192, "-"), ("cfg4_offloaded", 2, 1, 64, "pull"), ("cfg5", 3, 2, None, "pull"),
     ("cfg5_top2", 3, 2, None, "pull"), ("cfg5_top2", 3, 2, None, "memcpy"),
+    ("sweep64_k4", 2, 2, None, "pull"), ("sweep64_k16", 2, 1, None, "memcpy"), ("sweep64_k64", 2, 2, None, "pull"),
 ])
 def test_switch_shaped_stacks(hx, name, blocks, steps, sample, fetch):
     """Full d_model / d_ff / E / T of the Switch-shaped workloads; the number of blocks and steps

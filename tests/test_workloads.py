@@ -58,3 +58,12 @@ def test_gate_list_has_one_conventional_gate_and_L_minus_1_pregates():
     assert len(gates) == w.n_blocks
     assert np.array_equal(gates[0][0], W.gate0_weight(w))
     assert np.array_equal(gates[3][0], W.pregate_weight(w, 2))
+
+
+def test_activated_expert_sweep_points_share_weights_and_differ_only_in_top_k():
+    pts = [W.CONFIGS[f"sweep64_k{k}"] for k in W.SWEEP_K]
+    assert [p.top_k for p in pts] == [1, 2, 4, 8, 16, 32, 64]
+    a, b = pts[0], pts[-1]
+    assert (a.d_model, a.d_ff, a.n_experts, a.tokens, a.index) == (768, 3072, 64, 1, b.index) and b.top_k == b.n_experts
+    assert np.array_equal(W.pregate_weight(a, 0), W.pregate_weight(b, 0))
+    assert np.array_equal(W.step_input(a, 3), W.step_input(b, 3))

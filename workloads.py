@@ -74,6 +74,13 @@ CONFIGS = {
     "base8_prefill": Workload("base8_prefill", 5, 6, 768, 3072, 8, 1, 4096, 1, "bf16", 0.0, False),
 }
 
+# Activated-expert sweep (the paper's micro-benchmark on Switch-Base-64, Sec. VI-D): batch 1 and
+# the number of activated experts forced from 1 to all 64.  Every point shares one seed index, so
+# the weights are the same and only top_k changes.
+SWEEP_K = (1, 2, 4, 8, 16, 32, 64)
+for _k in SWEEP_K:
+    CONFIGS[f"sweep64_k{_k}"] = Workload(f"sweep64_k{_k}", 6, 6, 768, 3072, 64, _k, 1, 32, "bf16", 0.0, True)
+
 
 # ----------------------------------------------------------------------------- storage
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
