@@ -319,6 +319,31 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         for v in comp.values():
             v["block_latency_vs_pregated"] = v["block_latency_us"] / base
         out["systems"] = comp
+        # Pre-gate looking N = 2 / 3 blocks ahead (the paper's activation-level study, system
+        # side): experts are requested N blocks early and N + 1 generations stay resident.
+        dist = {"1": {"tokens_per_s": T * K / dt, "block_latency_us": 1e6 * dt / (K * L),
+                      "resident_generations": 2}}
+        for N in (2, 3):
+            if N >= L:
+                continue
+            stk = H.Stack(w, store, pregate_distance=N)
+            bufs = [stk.ctx.make_step_buffers(stk.gate_w, stk.gate_b, x_all[s % n_in], stk.y_blocks, idx_log[s],
+                                              stk.topk_prob, stk.row_of, stk.expert_offsets, stk.x_perm, stk.y_perm,
+                                              stk.workspace) for s in range(K)]
+            for s in range(Wm):
+                stk.ctx.stack_step(bufs[s % K], T, stk.compute, stk.copy)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for s in range(K):
+                stk.ctx.stack_step(bufs[s], T, stk.compute, stk.copy)
+            torch.cuda.synchronize()
+            dtn = time.perf_counter() - t0
+            assert stk.ctx.device_flags() == 0
+            dist[str(N)] = {"tokens_per_s": T * K / dtn, "block_latency_us": 1e6 * dtn / (K * L),
+                            "resident_generations": N + 1}
+            stk.close()
+            del stk, bufs
+        out["pregate_distance"] = dist
     if with_cpu:
         sample = cpu_steps or max(1, min(K, int(round(600.0 / (T * L * k)))))
         log(f"[bench] {w.name}: timing the CPU oracle on {sample} steps")

@@ -80,7 +80,14 @@ typedef struct {
                               per block that keep experts in HBM across steps; 0 = no cache (the
                               base design), at most PGMOE_MAX_CACHE_SLOTS.  Pull mode only. */
     int32_t cache_policy;  /* pgmoe_cache_policy: which cached expert a missing one replaces */
+    int32_t pregate_distance; /* N of Sec. VI-D "pre-gating to activate experts at different blocks":
+                              the pre-gate evaluated on x_i routes block i+N, so block i is routed
+                              from x_{max(0, i-N)} and N+1 block generations of experts are
+                              resident.  0 or 1 = the paper's default (next block); at most
+                              PGMOE_MAX_PREGATE_DISTANCE.  Used by pgmoe_stack_step with
+                              PGMOE_SCHED_PREGATED and by the slot pool's size. */
 } pgmoe_config;
+#define PGMOE_MAX_PREGATE_DISTANCE 3
 
 /* Replacement policies the paper evaluates.  A slot whose expert is used by the current fetch
  * is never a victim; empty slots are filled first (lowest index); ties go to the lowest slot.
@@ -95,7 +102,7 @@ typedef struct {
     int32_t n_unique;       /* distinct experts selected */
     int32_t n_copied;       /* experts actually copied (== n_unique in the base design) */
     int64_t bytes_copied;   /* n_copied * expert_bytes */
-    int32_t resident_slots; /* slots holding live experts over both generations right after
+    int32_t resident_slots; /* slots holding live experts over all generations right after
                                this fetch was issued: the quantity the peak-memory rule bounds
                                (cache slots, when a cache is configured, come on top) */
     int32_t cache_hits;     /* selected experts found in the block's cache (0 without a cache) */
@@ -150,13 +157,13 @@ int pgmoe_register_host_experts(pgmoe_ctx *ctx, const void *host_base, size_t ex
 int pgmoe_register_resident_experts(pgmoe_ctx *ctx, const void *dev_base, size_t expert_stride,
                                     size_t block_stride);
 /* Copy the experts that `topk_idx` (dev [T,k], produced on compute_stream) selects for
- * `block` into that block's slot generation (block & 1).  The j-th smallest selected expert
- * id goes to slot j.  Blocks 0, 1 and the odd blocks are copied on copy_stream, even blocks
- * from 2 on on a second copy stream the context owns (so that consecutive blocks' migrations
- * do not queue behind each other);
- * passing copy_stream == compute_stream instead runs the copy in plain stream order on
+ * `block` into that block's slot generation (block mod (pregate_distance + 1)).  The j-th
+ * smallest selected expert id goes to slot j.  Blocks 0..N (N = pregate_distance) are copied
+ * on copy_stream; from block N+1 on the blocks alternate between a second copy stream the
+ * context owns and copy_stream (so that consecutive blocks' migrations do not queue behind
+ * each other); passing copy_stream == compute_stream instead runs the copy in plain stream order on
  * compute_stream (an exposed fetch, as block 0's).  The copy first waits for compute_stream to
- * have produced the indices and for the FFN that last used this generation (block-2, or the
+ * have produced the indices and for the FFN that last used this generation (block-N-1, or the
  * previous step's) to have finished; pgmoe_expert_ffn(block) waits for the copy.
  *   default (pull) mode : one kernel on copy_stream reads the indices, forms the distinct
  *       expert list and pulls the blobs out of the pinned host store over the host link.
@@ -236,7 +243,10 @@ int pgmoe_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, con
  *               combine on the compute stream, x_{i+1} = x_i + y_i
  *   block L-1 : no gate.
  * gate_w[0] / gate_b[0] is block 0's conventional gate, gate_w[g] / gate_b[g] for g >= 1 the
- * pre-gate that sits in block g-1 (routes block g).  Arrays of pointers are host arrays of
+ * pre-gate that sits in block g-1 (routes block g).
+ * With pregate_distance N > 1 the gate that routes block g is evaluated on x_{max(0, g-N)}:
+ * block 0 runs the gates of blocks 0..N on x_0 and queues their fetches back to back, block
+ * i >= 1 runs the gate of block i+N; the last N blocks run none.  Arrays of pointers are host arrays of
  * device pointers; gate_b or any gate_b[g] may be NULL. */
 /* Schedules of pgmoe_stack_step.  PREGATED is the paper's method and the default.  The other
  * two are the paper's comparison systems on the same kernels (Sec. III and the timeline figure

@@ -173,17 +173,23 @@ def block(x, p, idx, experts: dict, d_ff: int, threads: int = 0) -> np.ndarray:
 
 
 # ------------------------------------------------------------------ stack of blocks
-def routing_source(i: int, wiring: str = "pregated") -> int:
+def routing_source(i: int, wiring: str = "pregated", distance: int = 1) -> int:
     """Index of the hidden state that routes block i.
 
     "pregated" (Sec. IV-B): x_0 for block 0 (its own conventional gate), x_{i-1} afterwards
-    (the pre-gate of block i-1).  "conventional" (Sec. II-B, the wiring of the paper's
-    comparison systems): every block is routed by its own gate on its own input x_i."""
+    (the pre-gate of block i-1).  With a pre-gate that looks `distance` = N blocks ahead
+    (Sec. VI-D, activation level N) block i is routed from x_{i-N}; the first N blocks have no
+    block that far behind them and are routed from x_0, the earliest state there is (N = 1
+    gives back the rule above, N = 0 the conventional wiring).
+    "conventional" (Sec. II-B, the wiring of the paper's comparison systems): every block is
+    routed by its own gate on its own input x_i."""
     if wiring == "conventional":
         return i
     if wiring != "pregated":
         raise ValueError(wiring)
-    return 0 if i == 0 else i - 1
+    if distance < 0:
+        raise ValueError(distance)
+    return max(0, i - distance)
 
 
 def block_from_states(x_route, x_cur, gate_w, gate_b, k: int, get_expert: Callable[[int], tuple],
@@ -198,17 +204,18 @@ def block_from_states(x_route, x_cur, gate_w, gate_b, k: int, get_expert: Callab
 
 
 def stack_forward(x0, gates: Sequence[tuple], k: int, get_expert: Callable[[int, int], tuple],
-                  d_ff: int, threads: int = 0, wiring: str = "pregated"):
+                  d_ff: int, threads: int = 0, wiring: str = "pregated", distance: int = 1):
     """Free-running oracle chain over L = len(gates) blocks.
 
-    gates[0] = (W, bias) of block 0's conventional gate; gates[i], i >= 1, = pre-gate i-1
-    (with wiring="conventional": gates[i] is block i's own gate).
+    gates[i] = (W, bias) of the gate that routes block i: block 0's conventional gate, then the
+    pre-gates (gates[i] sits in block max(0, i - distance)); with wiring="conventional"
+    gates[i] is block i's own gate.
     get_expert(block, e) -> (W1, W2).  Returns per-block dicts with x_in, gate, route, y,
     and the final hidden state."""
     xs = [_d(x0)]
     out = []
     for i, (gw, gb) in enumerate(gates):
-        src = xs[routing_source(i, wiring)]
+        src = xs[routing_source(i, wiring, distance)]
         res = block_from_states(src, xs[i], gw, gb, k, lambda e, i=i: get_expert(i, e), d_ff, threads)
         res["x_in"] = xs[i]
         out.append(res)

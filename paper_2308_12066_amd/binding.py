@@ -20,6 +20,7 @@ FLAG_FETCH_MEMCPY = 2
 SCHED_PREGATED, SCHED_ON_DEMAND, SCHED_PREFETCH_ALL = 0, 1, 2
 CACHE_LRU, CACHE_LFU, CACHE_LIFO = 0, 1, 2
 MAX_CACHE_SLOTS = 64
+MAX_PREGATE_DISTANCE = 3
 MAX_EXPERTS = 256
 
 EXPORTS = [
@@ -34,7 +35,8 @@ EXPORTS = [
 class Config(Structure):
     _fields_ = [("d_model", c_int32), ("d_ff", c_int32), ("n_experts", c_int32), ("top_k", c_int32),
                 ("n_blocks", c_int32), ("max_tokens", c_int32), ("dtype", c_int32), ("slots_per_gen", c_int32),
-                ("flags", c_uint32), ("cache_slots", c_int32), ("cache_policy", c_int32)]
+                ("flags", c_uint32), ("cache_slots", c_int32), ("cache_policy", c_int32),
+                ("pregate_distance", c_int32)]
 
 
 class FetchStats(Structure):
@@ -136,9 +138,9 @@ def last_error(ctx=None) -> str:
 
 
 def make_config(d_model, d_ff, n_experts, top_k, n_blocks, max_tokens, dtype, slots_per_gen=0, flags=0,
-                cache_slots=0, cache_policy=0) -> Config:
+                cache_slots=0, cache_policy=0, pregate_distance=0) -> Config:
     return Config(d_model, d_ff, n_experts, top_k, n_blocks, max_tokens, dtype, slots_per_gen, flags, cache_slots,
-                  cache_policy)
+                  cache_policy, pregate_distance)
 
 
 def expert_bytes(cfg: Config) -> int:

@@ -49,6 +49,8 @@ int check_config(const pgmoe_config *c, char *buf, size_t n) {
     if (c->cache_slots < 0 || c->cache_slots > PGMOE_MAX_CACHE_SLOTS || c->cache_slots > c->n_experts)
         BAD("cache_slots=%d outside 0..min(%d, n_experts)", c->cache_slots, PGMOE_MAX_CACHE_SLOTS);
     if (c->cache_policy < PGMOE_CACHE_LRU || c->cache_policy > PGMOE_CACHE_LIFO) BAD("cache_policy=%d unknown", c->cache_policy);
+    if (c->pregate_distance < 0 || c->pregate_distance > PGMOE_MAX_PREGATE_DISTANCE)
+        BAD("pregate_distance=%d outside 0..%d", c->pregate_distance, PGMOE_MAX_PREGATE_DISTANCE);
     if (c->cache_slots > 0 && (c->flags & PGMOE_FLAG_FETCH_MEMCPY))
         BAD("the expert cache is kept by the device-side pull engine: not available with PGMOE_FLAG_FETCH_MEMCPY");
     return PGMOE_OK;
@@ -157,6 +159,8 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
     c->elem = cfg->dtype == PGMOE_F32 ? 4 : 2;
     c->expert_bytes = pgmoe_expert_bytes(cfg);
     c->slots = cfg->slots_per_gen > 0 ? cfg->slots_per_gen : default_slots(*cfg);
+    c->distance = cfg->pregate_distance > 0 ? cfg->pregate_distance : 1;
+    c->n_gen = c->distance + 1;
     c->store_mode = STORE_NONE;
     c->err[0] = 0;
     for (int g = 0; g < kGen; ++g) {

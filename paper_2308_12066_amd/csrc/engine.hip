@@ -3,15 +3,17 @@
 // Sec. IV-C of the paper: all experts live in host memory; once the pre-gate of block N has
 // picked block N+1's experts, only those are copied to the GPU while block N executes, and
 // the GPU holds the activated experts of two consecutive blocks at most.  Here that is a
-// slot pool of two generations (generation = block & 1).  Read-after-write: the FFN of a
+// slot pool of two generations (generation = block & 1; N + 1 generations, block mod (N + 1),
+// when the pre-gate looks N blocks ahead).  Read-after-write: the FFN of a
 // block waits on the generation's fetch_done event (unless the fetch ran on the FFN's own
 // stream).  Write-after-read: a fetch into a generation must not start before the FFN that
 // read it last has finished; the indices the fetch depends on are produced on the compute
 // stream after that FFN, so waiting for them covers it, and only when the FFN ran on some
 // other stream is an extra event recorded there (at fetch time, behind the FFN) and waited on.
-// Even blocks from block 2 on are fetched on an internal second copy stream, so the migration
-// of block i+1 does not queue behind that of block i: the host link stays busy across the
+// Every second block from block N+1 on is fetched on an internal second copy stream, so the
+// migration of block i+1 does not queue behind that of block i: the host link stays busy across the
 // hand-over (two pull kernels share the link while they overlap).
+#include <algorithm>
 #include <chrono>
 #include <new>
 
@@ -68,7 +70,7 @@ int pgmoe_register_host_experts(pgmoe_ctx *ctx, const void *host_base, size_t ex
         PG_HIP(ctx, hipHostGetDevicePointer(&dev_view, const_cast<void *>(host_base), 0));
         ctx->store_dev = (const char *)dev_view;
         if (!ctx->slot_pool) {
-            const size_t bytes = (size_t)kGen * ctx->slots * ctx->expert_bytes;
+            const size_t bytes = (size_t)ctx->n_gen * ctx->slots * ctx->expert_bytes;
             PG_HIP(ctx, hipMalloc((void **)&ctx->slot_pool, bytes));
         }
         if (ctx->cfg.cache_slots > 0 && !ctx->cache_pool) {
@@ -129,9 +131,9 @@ static int fetch_impl(pgmoe_ctx *ctx, const char *fn, int block, bool all, const
     if (ctx->host_only) return fail(ctx, PGMOE_ENODEVICE, "%s: context is host-only, nothing can be launched", fn);
     hipStream_t cs = (hipStream_t)compute_stream, ps = (hipStream_t)copy_stream;
     const int n = all ? 0 : T * ctx->cfg.top_k;
-    const int gen = block & 1;
+    const int gen = block % ctx->n_gen;
     const bool inline_fetch = ps == cs;  // exposed fetch on the compute stream itself: plain stream order
-    if (!inline_fetch && gen == 0 && block > 1) ps = ctx->copy2;  // blocks 0,1 queue on the caller's stream, then alternate
+    if (!inline_fetch && block > ctx->distance && ((block - ctx->distance) & 1)) ps = ctx->copy2;  // blocks 0..N queue on the caller's stream, then alternate
     BlockStats &st = ctx->stats[block];
     st = BlockStats();
 
@@ -216,9 +218,12 @@ static int fetch_impl(pgmoe_ctx *ctx, const char *fn, int block, bool all, const
     st.s.n_unique = nu;
     st.s.n_copied = nu;
     st.s.bytes_copied = (int64_t)nu * (int64_t)ctx->expert_bytes;
-    // the other generation is live only if it holds the block that executes while this fetch
-    // runs (block - 1); anything else in it is left over from an earlier pass
-    st.s.resident_slots = nu + (ctx->fetched_block[gen ^ 1] == block - 1 ? ctx->live_slots[gen ^ 1] : 0);
+    // another generation is live only if it holds one of the N blocks that execute before
+    // this one (block - N .. block - 1); anything else is left over from an earlier pass
+    st.s.resident_slots = nu;
+    for (int g = 0; g < ctx->n_gen; ++g)
+        if (g != gen && ctx->fetched_block[g] >= block - ctx->distance && ctx->fetched_block[g] < block && ctx->fetched_block[g] >= 0)
+            st.s.resident_slots += ctx->live_slots[g];
     if (n_unique_out) *n_unique_out = nu;
     return PGMOE_OK;
 }
@@ -256,14 +261,19 @@ int pgmoe_get_fetch_stats(pgmoe_ctx *ctx, int block, pgmoe_fetch_stats *out) {
         }
         if (st.pulled) {
             // the pull kernel left the distinct-expert counts on the device
-            PG_HIP(ctx, hipStreamSynchronize(ctx->fetch_stream[block & 1]));
-            int32_t u[2] = {0, 0};
-            PG_HIP(ctx, hipMemcpy(&u[0], ctx->dev_unique + block, sizeof(int32_t), hipMemcpyDeviceToHost));
-            const bool prev_live = block > 0 && ctx->stats[block - 1].pulled;
-            if (prev_live) PG_HIP(ctx, hipMemcpy(&u[1], ctx->dev_unique + block - 1, sizeof(int32_t), hipMemcpyDeviceToHost));
-            int copied = u[0] < ctx->slots ? u[0] : ctx->slots;
-            st.s.n_unique = u[0];
-            st.s.resident_slots = copied + (u[1] < ctx->slots ? u[1] : ctx->slots);
+            PG_HIP(ctx, hipStreamSynchronize(ctx->fetch_stream[block % ctx->n_gen]));
+            int32_t u0 = 0;
+            PG_HIP(ctx, hipMemcpy(&u0, ctx->dev_unique + block, sizeof(int32_t), hipMemcpyDeviceToHost));
+            int copied = u0 < ctx->slots ? u0 : ctx->slots;
+            st.s.n_unique = u0;
+            st.s.resident_slots = copied;
+            // plus the generations of the N blocks that execute before this one
+            for (int b = block - 1; b >= 0 && b >= block - ctx->distance; --b) {
+                if (!ctx->stats[b].pulled) continue;
+                int32_t ub = 0;
+                PG_HIP(ctx, hipMemcpy(&ub, ctx->dev_unique + b, sizeof(int32_t), hipMemcpyDeviceToHost));
+                st.s.resident_slots += ub < ctx->slots ? ub : ctx->slots;
+            }
             if (st.cached) {  // unique, copies, hits as the cache-aware kernel counted them
                 int32_t cs3[3] = {0, 0, 0};
                 PG_HIP(ctx, hipMemcpy(cs3, ctx->cache_stats + (size_t)block * 4, sizeof cs3, hipMemcpyDeviceToHost));
@@ -328,7 +338,7 @@ int pgmoe_slot_address(pgmoe_ctx *ctx, int block, int slot, void **dev_out) {
     if (!dev_out) return fail(ctx, PGMOE_EINVAL, "%s: dev_out is NULL", fn);
     if (slot < 0 || slot >= ctx->slots) return fail(ctx, PGMOE_EINVAL, "%s: slot=%d outside 0..%d", fn, slot, ctx->slots - 1);
     if (!ctx->slot_pool) return fail(ctx, PGMOE_ESTATE, "%s: no slot pool (register a host expert store first)", fn);
-    *dev_out = ctx->slot_pool + ((size_t)(block & 1) * ctx->slots + slot) * ctx->expert_bytes;
+    *dev_out = ctx->slot_pool + ((size_t)(block % ctx->n_gen) * ctx->slots + slot) * ctx->expert_bytes;
     return PGMOE_OK;
 }
 
@@ -351,7 +361,7 @@ static int expert_ffn_impl(pgmoe_ctx *ctx, int block, const void *x_perm, const 
     if (ctx->store_mode == STORE_RESIDENT)
         return launch_ffn(ctx, ctx->store_base + (size_t)block * ctx->block_stride, ctx->expert_stride, false,
                           ctx->cfg.n_experts, x_perm, expert_offsets, n_rows, y_perm, workspace, s, keep_partials);
-    const int gen = block & 1;
+    const int gen = block % ctx->n_gen;
     if (ctx->fetched_block[gen] != block)
         return fail(ctx, PGMOE_ESTATE, "%s: block %d was not fetched (generation holds block %d)", fn, block, ctx->fetched_block[gen]);
     if (ctx->trace) PG_HIP(ctx, hipEventRecord(ctx->ev_ready[block], s));
@@ -442,30 +452,29 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     }
 
     if (ctx->trace) PG_HIP(ctx, hipEventRecord(ctx->ev_c0[0], (hipStream_t)compute_stream));
-    // Block 0: its own (conventional) gate and, on the same input, pre-gate 0 for block 1.  Both
-    // routings are known before anything can execute, so block 0's exposed fetch and block 1's
-    // fetch are queued back to back on the copy stream: the link never idles between them.
-    rc = pgmoe_pregate_topk(ctx, x_at(0), io->gate_w[0], bias_at(0), T, idx_at(0), prob_at(0), nullptr, compute_stream);
-    if (rc) return rc;
-    if (L > 1) {
-        rc = pgmoe_pregate_topk(ctx, x_at(0), io->gate_w[1], bias_at(1), T, idx_at(1), prob_at(1), nullptr, compute_stream);
+    // Block 0: its own (conventional) gate and, on the same input, the pre-gates of blocks
+    // 1..N (N = pre-gate distance, 1 in the paper's design).  All these routings are known
+    // before anything can execute, so block 0's exposed fetch and the fetches of blocks 1..N are
+    // queued back to back on the copy stream: the link never idles between them.
+    const int N = ctx->distance;
+    const int head = std::min(N, L - 1);
+    for (int g = 0; g <= head; ++g) {
+        rc = pgmoe_pregate_topk(ctx, x_at(0), io->gate_w[g], bias_at(g), T, idx_at(g), prob_at(g), nullptr, compute_stream);
         if (rc) return rc;
     }
-    rc = pgmoe_fetch_experts(ctx, 0, idx_at(0), T, compute_stream, copy_stream, nullptr);
-    if (rc) return rc;
-    if (L > 1) {
-        rc = pgmoe_fetch_experts(ctx, 1, idx_at(1), T, compute_stream, copy_stream, nullptr);
+    for (int g = 0; g <= head; ++g) {
+        rc = pgmoe_fetch_experts(ctx, g, idx_at(g), T, compute_stream, copy_stream, nullptr);
         if (rc) return rc;
     }
 
     for (int i = 0; i < L; ++i) {
         if (ctx->trace && i > 0) PG_HIP(ctx, hipEventRecord(ctx->ev_c0[i], (hipStream_t)compute_stream));
-        // pre-gate of block i routes block i+1; its experts start moving before block i executes
-        if (i > 0 && i + 1 < L) {
-            rc = pgmoe_pregate_topk(ctx, x_at(i), io->gate_w[i + 1], bias_at(i + 1), T, idx_at(i + 1), prob_at(i + 1), nullptr,
-                                    compute_stream);
+        // the pre-gate of block i routes block i+N; its experts start moving before block i executes
+        if (i > 0 && i + N < L) {
+            const int g = i + N;
+            rc = pgmoe_pregate_topk(ctx, x_at(i), io->gate_w[g], bias_at(g), T, idx_at(g), prob_at(g), nullptr, compute_stream);
             if (rc) return rc;
-            rc = pgmoe_fetch_experts(ctx, i + 1, idx_at(i + 1), T, compute_stream, copy_stream, nullptr);
+            rc = pgmoe_fetch_experts(ctx, g, idx_at(g), T, compute_stream, copy_stream, nullptr);
             if (rc) return rc;
         }
         int32_t *row_of = io->row_of + (size_t)i * nk;

@@ -224,7 +224,7 @@ __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_cache_kernel(
 size_t cache_state_bytes(const pgmoe_config &c) { return (size_t)c.n_blocks * 2 * CACHE_STATE_INTS * sizeof(int32_t); }
 
 int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, int n, hipStream_t s) {
-    const int gen = block & 1;
+    const int gen = block % ctx->n_gen;
     char *gen_base = ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes;
     const char *src = ctx->store_dev + (size_t)block * ctx->block_stride;
     if (ctx->cfg.cache_slots > 0 && !all) {

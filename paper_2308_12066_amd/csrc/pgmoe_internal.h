@@ -14,7 +14,7 @@ namespace pgmoe {
 
 enum StoreMode { STORE_NONE = 0, STORE_HOST = 1, STORE_RESIDENT = 2 };
 
-constexpr int kGen = 2;  // block generations resident at once (current + next block)
+constexpr int kGen = PGMOE_MAX_PREGATE_DISTANCE + 1;  // most block generations resident at once
 
 // Device-side sticky condition bits (see pgmoe_device_flags).
 constexpr uint32_t kFlagNaN = 1u;
@@ -40,6 +40,8 @@ struct pgmoe_ctx {
     size_t elem;          // bytes per activation / weight element
     size_t expert_bytes;  // 2*d*f*elem
     int slots;            // slots per generation
+    int distance;         // pre-gate distance N (>= 1)
+    int n_gen;            // N + 1 block generations: block b lives in generation b % n_gen
 
     // expert store
     int store_mode;
@@ -47,7 +49,7 @@ struct pgmoe_ctx {
     size_t expert_stride, block_stride;
 
     // device resources
-    char *slot_pool;       // [kGen][slots][expert_bytes]
+    char *slot_pool;       // [n_gen][slots][expert_bytes]
     uint32_t *dev_flags;   // sticky condition bits
     int32_t *dev_unique;   // [n_blocks] distinct experts found by the pull kernel (dev_flags + 64 bytes)
     const char *store_dev; // device-visible address of the pinned host store

@@ -19,9 +19,10 @@ def abi_dtype(w: W.Workload) -> int:
     return B.F32 if w.dtype == "f32" else B.BF16
 
 
-def config_for(w: W.Workload, max_tokens=None, slots_per_gen=0, flags=0, cache_slots=0, cache_policy=0) -> B.Config:
+def config_for(w: W.Workload, max_tokens=None, slots_per_gen=0, flags=0, cache_slots=0, cache_policy=0,
+               pregate_distance=0) -> B.Config:
     return B.make_config(w.d_model, w.d_ff, w.n_experts, w.top_k, w.n_blocks, max_tokens or w.tokens, abi_dtype(w),
-                         slots_per_gen, flags, cache_slots, cache_policy)
+                         slots_per_gen, flags, cache_slots, cache_policy, pregate_distance)
 
 
 def to_device(a: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
@@ -92,10 +93,10 @@ class Stack:
     """One pre-gated MoE stack on the GPU: context, gate tensors, per-step buffers, two streams."""
 
     def __init__(self, w: W.Workload, store: ExpertStore, gates=None, max_tokens=None, slots_per_gen=0, flags=0,
-                 cache_slots=0, cache_policy=0):
+                 cache_slots=0, cache_policy=0, pregate_distance=0):
         self.w = w
         self.cfg = config_for(w, max_tokens=max_tokens, slots_per_gen=slots_per_gen, flags=flags,
-                              cache_slots=cache_slots, cache_policy=cache_policy)
+                              cache_slots=cache_slots, cache_policy=cache_policy, pregate_distance=pregate_distance)
         self.ctx = B.Context(self.cfg)
         self.store = store
         T, d, k, E, L = self.cfg.max_tokens, w.d_model, w.top_k, w.n_experts, w.n_blocks

@@ -36,7 +36,8 @@ def cfg(**kw):
 
 @pytest.mark.parametrize("bad", [dict(dtype=7), dict(d_model=0), dict(d_model=96), dict(d_ff=100), dict(n_experts=0),
                                  dict(n_experts=257), dict(top_k=0), dict(top_k=9), dict(n_blocks=0),
-                                 dict(max_tokens=0), dict(slots_per_gen=9), dict(flags=64), dict(d_model=4096)])
+                                 dict(max_tokens=0), dict(slots_per_gen=9), dict(flags=64), dict(d_model=4096),
+                                 dict(pregate_distance=4), dict(pregate_distance=-1)])
 def test_create_rejects_bad_config(bad):
     with pytest.raises(B.PgmoeError) as ei:
         B.Context(cfg(**bad))

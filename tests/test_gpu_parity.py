@@ -269,7 +269,7 @@ def test_combine_matches_definition(hx, dtype, T, d, k):
 
 
 # ------------------------------------------------------------------------------ whole stack
-def check_stack_step(H, w, stack, gates, expert_cache, sample_tokens=None, label="", wiring="pregated"):
+def check_stack_step(H, w, stack, gates, expert_cache, sample_tokens=None, label="", wiring="pregated", distance=1):
     """Block-by-block check of one executed step against the oracle evaluated on the GPU's own
     hidden states (x_{i-1} routes block i, x_i feeds its experts).  Returns statistics."""
     torch.cuda.synchronize()
@@ -283,7 +283,7 @@ def check_stack_step(H, w, stack, gates, expert_cache, sample_tokens=None, label
     stats = dict(near_tie=0, tokens=0, max_err=0.0, max_prob_err=0.0)
     for i in range(L):
         gw, gb = gates[i]
-        o = R.gate(xs[R.routing_source(i, wiring)], gw, gb, k)
+        o = R.gate(xs[R.routing_source(i, wiring, distance)], gw, gb, k)
         exact = o["gaps"].min(axis=1) >= TIE
         stats["near_tie"] += int((~exact).sum())
         stats["tokens"] += T
@@ -306,18 +306,22 @@ def check_stack_step(H, w, stack, gates, expert_cache, sample_tokens=None, label
     return stats
 
 
-def make_stack(H, w, threads=HOST_THREADS, flags=0):
+def make_stack(H, w, threads=HOST_THREADS, flags=0, pregate_distance=0, weight_scale=1.0):
+    """weight_scale: a power of two (keeps bf16 values exact) that makes the blocks' outputs
+    comparable to the hidden state, so that consecutive hidden states route differently."""
     cfg = H.config_for(w, flags=flags)
     cache = {}
 
     def get(b, e):
         w1, w2 = W.expert_weights(w, b, e)
+        if weight_scale != 1.0:
+            w1, w2 = w1 * np.float32(weight_scale), w2 * np.float32(weight_scale)
         cache[(b, e)] = (W.to_bf16_bits(w1), W.to_bf16_bits(w2)) if w.dtype == "bf16" else (w1, w2)
         return w1, w2
 
     store = H.ExpertStore(w, cfg, threads=threads, get_expert=get)
     gates = W.gate_tensors(w)
-    stack = H.Stack(w, store, gates=gates, flags=flags)
+    stack = H.Stack(w, store, gates=gates, flags=flags, pregate_distance=pregate_distance)
     return stack, gates, (lambda b, e: cache[(b, e)])
 
 
@@ -371,6 +375,41 @@ def test_switch_shaped_stacks(hx, name, blocks, steps, sample, fetch):
                 assert fs.resident_slots <= u + max(nb, default=0)      # two generations at most
     say(f"  {name}: near-tie tokens exempted {near} of {tot}")
     assert stack.ctx.device_flags() == 0
+    stack.close()
+
+
+@pytest.mark.parametrize("distance,fetch,T,E,k", [(2, "pull", 16, 16, 1), (3, "pull", 5, 8, 2), (2, "memcpy", 16, 16, 1),
+                                                   (3, "memcpy", 33, 12, 1)])
+def test_pregate_distance_routes_from_the_earlier_state_and_keeps_more_generations(hx, distance, fetch, T, E, k):
+    """Pre-gate looking N = 2 / 3 blocks ahead (Sec. VI-D): block i is routed from x_{max(0,i-N)},
+    its experts are fetched N blocks early and N + 1 generations are resident."""
+    H, B = hx
+    L = 7
+    w = small_workload("bf16", T, 128, 256, E, k, L=L, offloaded=True, index=46 + distance)
+    say(f"pre-gate distance {distance}: fetch={fetch} T={T} E={E} k={k} L={L}")
+    stack, gates, cache = make_stack(H, w, flags=B.FLAG_FETCH_MEMCPY if fetch == "memcpy" else 0, pregate_distance=distance,
+                                     weight_scale=4.0)
+    for s in range(3):
+        stack.set_input(W.step_input(w, s))
+        stack.step()
+        st = check_stack_step(H, w, stack, gates, cache, label=f"distance {distance} step {s}", distance=distance)
+        say(f"  step {s}: {st}")
+        idx = stack.topk_idx.cpu().numpy()
+        u = [len(np.unique(idx[b])) for b in range(L)]
+        for b in range(L):
+            fs = stack.ctx.fetch_stats(b)
+            assert fs.n_unique == u[b] and fs.bytes_copied == u[b] * w.expert_bytes
+            assert u[b] <= fs.resident_slots <= sum(u[max(0, b - distance): b + 1])    # N + 1 generations at most
+            # the generation holds exactly the selected experts, in ascending order
+            for j, e in enumerate(np.unique(idx[b])):
+                if b >= L - 1 - distance:      # still resident after the step: not overwritten by a later block
+                    got = _device_bytes(stack.ctx.slot_address(b, j), w.expert_bytes)
+                    assert np.array_equal(got, stack.store.blob(b, int(e)))
+    assert stack.ctx.device_flags() == 0
+    # the wiring is really the distant one: on this data the default wiring selects differently
+    xs = H.to_numpy64(stack.x_states)
+    differs = any(not np.array_equal(R.gate(xs[max(0, i - 1)], gates[i][0], gates[i][1], k)["idx"], idx[i]) for i in range(2, L))
+    assert differs
     stack.close()
 
 

@@ -224,13 +224,16 @@ def test_missing_expert_is_an_error():
 
 
 # ----------------------------------------------------------------------- stack wiring
-def _numpy_stack(x0, gates, w1, w2, k, conventional=False):
-    """The pre-gated (or conventional) wiring written out by hand with explicit indices (numpy only)."""
+def _numpy_stack(x0, gates, w1, w2, k, conventional=False, table=None):
+    """The pre-gated (or conventional) wiring written out by hand with explicit indices (numpy only).
+    table: for every block, the index of the hidden state that routes it, spelled out."""
     L = len(gates)
     xs = [x0]
     ys, idxs = [], []
     for i in range(L):
         src = xs[i] if conventional else (xs[0] if i == 0 else xs[i - 1])
+        if table is not None:
+            src = xs[table[i]]
         y, _, _, idx = dense_masked(src, xs[i], gates[i][0], gates[i][1], w1[i], w2[i], k)
         ys.append(y)
         idxs.append(idx)
@@ -273,6 +276,29 @@ def test_conventional_wiring_matches_explicit_numpy_chain():
     np.testing.assert_allclose(x_last, xs[-1], atol=1e-11)
     pre, _ = R.stack_forward(x0, gates, k, lambda b, e: (w1[b, e], w2[b, e]), f)
     assert any(not np.array_equal(pre[i]["gate"]["idx"], idxs[i]) for i in range(1, L))   # the wirings differ
+
+
+@pytest.mark.parametrize("distance,table", [(2, [0, 0, 0, 1, 2, 3]), (3, [0, 0, 0, 0, 1, 2]), (1, [0, 0, 1, 2, 3, 4]),
+                                            (0, [0, 1, 2, 3, 4, 5])])
+def test_pregate_distance_wiring_matches_a_spelled_out_table(distance, table):
+    # Sec. VI-D, activation level N: the gate evaluated N blocks earlier routes the block; the
+    # expected source of every block is written out by hand above, not computed.
+    g = rng(37 + distance)
+    L, T, d, f, E, k = 6, 7, 8, 10, 5, 2
+    x0 = g.standard_normal((T, d))
+    gates = [(g.standard_normal((d, E)), g.standard_normal(E) * 0.2) for _ in range(L)]
+    w1 = g.standard_normal((L, E, d, f)) * 0.4
+    w2 = g.standard_normal((L, E, f, d)) * 0.4
+    assert [R.routing_source(i, "pregated", distance) for i in range(L)] == table
+    out, x_last = R.stack_forward(x0, gates, k, lambda b, e: (w1[b, e], w2[b, e]), f, distance=distance)
+    ys, idxs, xs = _numpy_stack(x0, gates, w1, w2, k, table=table)
+    for i in range(L):
+        assert np.array_equal(out[i]["gate"]["idx"], idxs[i]), f"routing of block {i}"
+        np.testing.assert_allclose(out[i]["y"], ys[i], atol=1e-10)
+    np.testing.assert_allclose(x_last, xs[-1], atol=1e-10)
+    if distance != 1:   # and it is a different computation from the default wiring on this data
+        base, _ = R.stack_forward(x0, gates, k, lambda b, e: (w1[b, e], w2[b, e]), f)
+        assert any(not np.array_equal(base[i]["gate"]["idx"], idxs[i]) for i in range(L))
 
 
 def test_pregate_reduces_to_conventional_gate_when_block_is_identity():
