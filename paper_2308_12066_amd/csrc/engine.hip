@@ -461,8 +461,6 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     for (int g = 0; g <= head; ++g) {
         rc = pgmoe_pregate_topk(ctx, x_at(0), io->gate_w[g], bias_at(g), T, idx_at(g), prob_at(g), nullptr, compute_stream);
         if (rc) return rc;
-    }
-    for (int g = 0; g <= head; ++g) {
         rc = pgmoe_fetch_experts(ctx, g, idx_at(g), T, compute_stream, copy_stream, nullptr);
         if (rc) return rc;
     }

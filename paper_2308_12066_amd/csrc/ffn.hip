@@ -237,6 +237,99 @@ __global__ __launch_bounds__(NW * 64) void ffn_fused_kernel(
     }
 }
 
+// Decode-sized variant (at most a few experts active, <= 16 rows each): one workgroup of four
+// wavefronts per (chunk, 32-column sub-slab of d_ff), every weight tile it needs requested before
+// anything else happens, so the kernel is one round of memory latency deep instead of a ring of
+// dependent rounds.  Phase A splits the d_model reduction over wavefront pairs (wave = n-tile
+// + 2 * k-half; the two halves are added in LDS, k-half 0 first), phase B gives each wavefront a
+// quarter of the output columns.  Always writes float32 partials (one per sub-slab).
+template <int KT>
+__global__ __launch_bounds__(256) void ffn_decode_kernel(
+    const __bf16 *__restrict__ x_perm, const int32_t *__restrict__ offsets, int E, int f,
+    const char *__restrict__ w_base, size_t w_stride, int slot_by_rank, int n_slots,
+    const unsigned long long *__restrict__ table, float *__restrict__ partial, int n_rows) {
+    constexpr int d = KT * 32;
+    constexpr int NTD = KT * 2;   // output n-tiles
+    constexpr int NA = KT / 2;    // phase-A tiles per wavefront
+    constexpr int NB = NTD / 4;   // phase-B tiles per wavefront
+    static_assert(KT % 2 == 0, "k split");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int cw = wave & 1, ks = wave >> 1;
+
+    const ChunkInfo ci = find_chunk(offsets, E, 16, blockIdx.x);
+    if (ci.nrows == 0) return;  // uniform over the workgroup
+    const char *wexp = table ? reinterpret_cast<const char *>(table[ci.expert])
+                             : w_base + (size_t)(slot_by_rank ? ci.slot : ci.expert) * w_stride;
+    const bool no_weights = table ? wexp == nullptr : (slot_by_rank && ci.slot >= n_slots);  // no slot: rows are zeroed
+    const int fs = blockIdx.y * 32;
+
+    bf16x8 ta[NA], tb[NB];
+    if (!no_weights) {
+        const bf16x8 *w1 = reinterpret_cast<const bf16x8 *>(wexp) + (((size_t)((fs >> 4) + cw) * KT) << 6) + lane;
+        const bf16x8 *w2 = reinterpret_cast<const bf16x8 *>(wexp + (size_t)d * f * 2) +
+                           (((size_t)(fs >> 5) * NTD + wave * NB) << 6) + lane;
+#pragma unroll
+        for (int i = 0; i < NA; ++i) ta[i] = w1[(size_t)(ks + 2 * i) << 6];
+#pragma unroll
+        for (int a = 0; a < NB; ++a) tb[a] = w2[(size_t)a << 6];
+    } else {
+#pragma unroll
+        for (int i = 0; i < NA; ++i) ta[i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int a = 0; a < NB; ++a) tb[a] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+
+    bf16x8 *xs = reinterpret_cast<bf16x8 *>(smem);                       // [KT][64] operand cells
+    floatx4 *hsum = reinterpret_cast<floatx4 *>(xs + (size_t)KT * 64);   // [2 k-halves][2 n-tiles][64]
+    {
+        constexpr int cells_per_row = d >> 3;
+        const uint4 *src = reinterpret_cast<const uint4 *>(x_perm + (size_t)ci.row0 * d);
+        uint4 *dst = reinterpret_cast<uint4 *>(xs);
+        for (int i = tid; i < 16 * cells_per_row; i += 256) {
+            const int m = i / cells_per_row, k8 = i - m * cells_per_row;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (m < ci.nrows) v = src[(size_t)m * cells_per_row + k8];
+            dst[((k8 >> 2) << 6) + m + 16 * (k8 & 3)] = v;
+        }
+    }
+    lds_barrier();
+
+    // ---- phase A: 16 hidden features (n-tile cw of the sub-slab) over this wavefront's k-tiles
+    floatx4 hacc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+        hacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ta[i], xs[((ks + 2 * i) << 6) + lane], hacc, 0, 0, 0);
+    hsum[(ks * 2 + cw) * 64 + lane] = hacc;
+    lds_barrier();
+
+    // ---- hidden activation as phase-B operand: lane (token lane%16, k-group g = lane/16) needs
+    // features 8g .. 8g+7 of the 32, i.e. n-tile g/2, accumulator rows 4*q' + r for q' = 2*(g%2), +1
+    const int tok = lane & 15, g = lane >> 4;
+    bf16x8 hfrag;
+    {
+        const int src = (g >> 1) * 64 + (2 * (g & 1)) * 16 + tok;
+        const floatx4 lo = hsum[src] + hsum[128 + src];
+        const floatx4 hi = hsum[src + 16] + hsum[128 + src + 16];
+        hfrag[0] = (__bf16)fmaxf(lo.x, 0.f);
+        hfrag[1] = (__bf16)fmaxf(lo.y, 0.f);
+        hfrag[2] = (__bf16)fmaxf(lo.z, 0.f);
+        hfrag[3] = (__bf16)fmaxf(lo.w, 0.f);
+        hfrag[4] = (__bf16)fmaxf(hi.x, 0.f);
+        hfrag[5] = (__bf16)fmaxf(hi.y, 0.f);
+        hfrag[6] = (__bf16)fmaxf(hi.z, 0.f);
+        hfrag[7] = (__bf16)fmaxf(hi.w, 0.f);
+    }
+
+    // ---- phase B: this wavefront's NB output n-tiles; lane holds token tok, columns 16*tile + 4*g + {0..3}
+    float *dst = partial + ((size_t)blockIdx.y * n_rows + (size_t)ci.row0 + tok) * d + (wave * NB) * 16 + 4 * g;
+#pragma unroll
+    for (int a = 0; a < NB; ++a) {
+        const floatx4 y = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tb[a], hfrag, floatx4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        if (tok < ci.nrows) *reinterpret_cast<floatx4 *>(dst + a * 16) = y;
+    }
+}
+
 // y_perm[row][c] = bf16( sum_p partial[p][row][c] ).  A workgroup of 256 threads covers 256/PL
 // float4 columns; its PL "p-lanes" each add every PL-th partial (p = pl, pl+PL, ...) and the PL
 // sub-sums are added in ascending order, so the result does not depend on scheduling.  PL is
@@ -465,6 +558,33 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
     }
     const FfnPlan p = plan_ffn(c, n_rows);
     const int kt = c.d_model / 32;
+    if (p.mt == 1 && p.nw == 2 && p.n_partial == c.d_ff / 32 && (kt == 24 || kt == 32) && !getenv("PGMOE_FFN_NO_DECODE")) {
+        // a few experts with at most 16 rows each, one partial per 32-column sub-slab
+        float *partial = (float *)workspace;
+        if ((size_t)p.n_partial * n_rows * c.d_model * 4 > ffn_workspace_bytes(c))
+            return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: %d partial sums of %d rows do not fit the workspace", p.n_partial, n_rows);
+        const int tslot = timing_slot(ctx);
+        if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_begin[tslot], s));
+        const dim3 grid(p.max_chunks, p.n_partial);
+        const size_t lds = (size_t)kt * 1024 + 4096;
+        if (kt == 24)
+            hipLaunchKernelGGL(ffn_decode_kernel<24>, grid, dim3(256), lds, s, (const __bf16 *)x_perm, offsets, c.n_experts, c.d_ff,
+                               w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, partial, n_rows);
+        else
+            hipLaunchKernelGGL(ffn_decode_kernel<32>, grid, dim3(256), lds, s, (const __bf16 *)x_perm, offsets, c.n_experts, c.d_ff,
+                               w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, partial, n_rows);
+        PG_HIP(ctx, hipGetLastError());
+        if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
+        if (keep_partials) {
+            *keep_partials = p.n_partial;
+            return PGMOE_OK;
+        }
+        const size_t total4 = (size_t)n_rows * c.d_model / 4;
+        hipLaunchKernelGGL(ffn_reduce_kernel<16>, dim3((unsigned)((total4 + 15) / 16)), dim3(256), 0, s, partial, p.n_partial, n_rows,
+                           c.d_model, (__bf16 *)y_perm);
+        PG_HIP(ctx, hipGetLastError());
+        return PGMOE_OK;
+    }
     if (c.d_ff % (16 * p.nw)) return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: d_ff=%d is not a multiple of the %d-column sub-slab", c.d_ff, 16 * p.nw);
 #define PG_CASE(MT_, KT_, NW_, D_) \
     if (p.mt == MT_ && kt == KT_ && p.nw == NW_) return launch_fused<MT_, KT_, NW_, D_>(ctx, p, w_base, w_stride, slot_by_rank, n_slots, x_perm, offsets, n_rows, y_perm, workspace, s, keep_partials, table)

@@ -221,6 +221,10 @@ FFN_CASES = [
     ("bf16", 1024, 4096, 6, [16, 1, 0, 31, 2, 14]),
     ("bf16", 768, 3072, 4, [40, 25, 33, 64]),                  # prefill-like rows per expert
     ("bf16", 512, 1024, 3, [200, 3, 90]),
+    # few active experts with <= 16 rows per chunk: the decode kernel (full chunk + second chunk, ragged, d_model 1024)
+    ("bf16", 768, 3072, 5, [17, 0, 0, 0, 2]),
+    ("bf16", 768, 3072, 4, [4, 0, 3, 0]),
+    ("bf16", 1024, 4096, 3, [1, 0, 2]),
 ]
 
 
