@@ -188,7 +188,7 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         "block_latency_us": 1e6 * dt / (K * L),
         "roofline": {"bound": "hbm", "achieved": ffn_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": ffn_gbps / HBM_PEAK_GBPS, "traffic": pmc_traffic(w.name),
-                     "kernel": "ffn_fused_kernel" if w.dtype == "bf16" else "ffn_f32_hidden_kernel+ffn_f32_out_kernel",
+                     "kernel": stack.ctx.ffn_kernel_name(T * k),
                      "launches": n_timed, "avg_launch_us": ffn_avg_us, "event_pair_us": raw_us,
                      "event_overhead_us": overhead_us, "algorithmic_bytes_per_launch": per_launch,
                      "ms_per_step_with_events": 1e3 * dt_events / K},

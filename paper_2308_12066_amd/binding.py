@@ -29,6 +29,7 @@ EXPORTS = [
     "pgmoe_register_resident_experts", "pgmoe_fetch_experts", "pgmoe_get_fetch_stats", "pgmoe_unique_experts",
     "pgmoe_permute", "pgmoe_expert_ffn", "pgmoe_combine", "pgmoe_stack_step", "pgmoe_device_flags",
     "pgmoe_ffn_timing_begin", "pgmoe_ffn_timing_end", "pgmoe_slot_address", "pgmoe_fetch_timing", "pgmoe_trace", "pgmoe_get_block_trace", "pgmoe_fetch_all_experts", "pgmoe_set_schedule",
+    "pgmoe_ffn_kernel_name",
 ]
 
 
@@ -96,6 +97,8 @@ def _load():
     L.pgmoe_stack_step.argtypes = [vp, POINTER(StepBuffers), i, vp, vp]
     L.pgmoe_device_flags.argtypes = [vp, POINTER(c_uint32)]
     L.pgmoe_ffn_timing_begin.argtypes = [vp, i]
+    L.pgmoe_ffn_kernel_name.argtypes = [vp, i]
+    L.pgmoe_ffn_kernel_name.restype = c_char_p
     L.pgmoe_fetch_timing.argtypes = [vp, i]
     L.pgmoe_trace.argtypes = [vp, i]
     L.pgmoe_fetch_all_experts.argtypes = [vp, i, vp, vp]
@@ -104,7 +107,7 @@ def _load():
     L.pgmoe_slot_address.argtypes = [vp, i, i, POINTER(vp)]
     L.pgmoe_ffn_timing_end.argtypes = [vp, POINTER(c_int), POINTER(c_float), POINTER(c_float)]
     for name in EXPORTS:
-        if name not in ("pgmoe_last_error", "pgmoe_expert_bytes", "pgmoe_workspace_bytes"):
+        if name not in ("pgmoe_last_error", "pgmoe_expert_bytes", "pgmoe_workspace_bytes", "pgmoe_ffn_kernel_name"):
             getattr(L, name).restype = c_int
     return L
 
@@ -253,6 +256,9 @@ class Context:
         f = c_uint32(0)
         self._check(lib.pgmoe_device_flags(self._h, byref(f)))
         return f.value
+
+    def ffn_kernel_name(self, n_rows: int) -> str:
+        return lib.pgmoe_ffn_kernel_name(self._h, n_rows).decode()
 
     def ffn_timing_begin(self, max_launches: int):
         self._check(lib.pgmoe_ffn_timing_begin(self._h, max_launches))

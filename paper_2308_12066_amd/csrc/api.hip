@@ -369,6 +369,11 @@ int pgmoe_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, con
     return launch_combine(ctx, y_perm, row_of, topk_prob, T, y, x_res, x_next, (hipStream_t)stream);
 }
 
+const char *pgmoe_ffn_kernel_name(const pgmoe_ctx *ctx, int n_rows) {
+    if (!ctx) return nullptr;
+    return ffn_kernel_name(ctx->cfg, n_rows < 1 ? 1 : n_rows);
+}
+
 int pgmoe_ffn_timing_begin(pgmoe_ctx *ctx, int max_launches) {
     const char *fn = "pgmoe_ffn_timing_begin";
     if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);

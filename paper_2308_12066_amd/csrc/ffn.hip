@@ -478,6 +478,18 @@ FfnPlan plan_ffn(const pgmoe_config &c, int n_rows) {
     return p;
 }
 
+// The decode-sized kernel serves launches of 16-row chunks split into one partial per
+// 32-column sub-slab (what plan_ffn picks when only a few experts are active).
+static bool uses_decode_kernel(const pgmoe_config &c, const FfnPlan &p) {
+    const int kt = c.d_model / 32;
+    return p.mt == 1 && p.nw == 2 && p.n_partial == c.d_ff / 32 && (kt == 24 || kt == 32) && !getenv("PGMOE_FFN_NO_DECODE");
+}
+
+const char *ffn_kernel_name(const pgmoe_config &c, int n_rows) {
+    if (c.dtype == PGMOE_F32) return "ffn_f32_hidden_kernel+ffn_f32_out_kernel";
+    return uses_decode_kernel(c, plan_ffn(c, n_rows)) ? "ffn_decode_kernel" : "ffn_fused_kernel";
+}
+
 size_t ffn_workspace_bytes(const pgmoe_config &c) {
     const int64_t max_rows = (int64_t)c.max_tokens * c.top_k;
     if (c.dtype == PGMOE_F32) return (size_t)max_rows * c.d_ff * 4;
@@ -558,7 +570,7 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
     }
     const FfnPlan p = plan_ffn(c, n_rows);
     const int kt = c.d_model / 32;
-    if (p.mt == 1 && p.nw == 2 && p.n_partial == c.d_ff / 32 && (kt == 24 || kt == 32) && !getenv("PGMOE_FFN_NO_DECODE")) {
+    if (uses_decode_kernel(c, p)) {
         // a few experts with at most 16 rows each, one partial per 32-column sub-slab
         float *partial = (float *)workspace;
         if ((size_t)p.n_partial * n_rows * c.d_model * 4 > ffn_workspace_bytes(c))

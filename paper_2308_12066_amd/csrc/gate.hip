@@ -264,28 +264,47 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_mfma_kernel(
 
     const bool tok_ok = n < nt;
     const __bf16 *xrow = x + (size_t)(t0 + (tok_ok ? n : 0)) * d + 8 * g;
-    for (int kt = wave; kt < KT; kt += 4) {
-        gbf16x8 a = *reinterpret_cast<const gbf16x8 *>(xrow + kt * 32);
-        if (!tok_ok) a = gbf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    // Register prefetch ring, PF k-tiles deep: the operands of k-tile i + PF are requested when
+    // k-tile i is consumed, so a wavefront pays the memory latency once, not once per k-tile.
+    // Stages past the last k-tile hold zeros (they add nothing).
+    constexpr int PF = NP == 1 ? 3 : 2;
+    const gbf16x8 zero8 = gbf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    gbf16x8 a_buf[PF], rows_buf[PF][NP][8];
+    auto request = [&](int kt, gbf16x8 &a, gbf16x8 (&rows)[NP][8]) {
+        const bool live = kt < KT;
+        a = (live && tok_ok) ? *reinterpret_cast<const gbf16x8 *>(xrow + kt * 32) : zero8;
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             const int cv = n + 16 * p;
-            gbf16x8 rows[8];
-            if (cv < ncv) {
+            if (live && cv < ncv) {
                 const gbf16x8 *src = reinterpret_cast<const gbf16x8 *>(w + (size_t)(kt * 32 + 8 * g) * E) + cv;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) rows[j] = src[(size_t)j * ncv];
+                for (int j = 0; j < 8; ++j) rows[p][j] = src[(size_t)j * ncv];
             } else {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) rows[j] = gbf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+                for (int j = 0; j < 8; ++j) rows[p][j] = zero8;
             }
+        }
+    };
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                gbf16x8 cell;
+    for (int st = 0; st < PF; ++st) request(wave + 4 * st, a_buf[st], rows_buf[st]);
+    for (int kt0 = wave; kt0 < KT; kt0 += 4 * PF) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) cell[j] = rows[j][q];
-                acc[p][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, cell, acc[p][q], 0, 0, 0);
-            }
+        for (int st = 0; st < PF; ++st) {
+            const gbf16x8 a = a_buf[st];
+            gbf16x8 cells[NP][8];
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) cells[p][q][j] = rows_buf[st][p][j][q];
+            request(kt0 + 4 * (st + PF), a_buf[st], rows_buf[st]);
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    acc[p][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, cells[p][q], acc[p][q], 0, 0, 0);
         }
     }
     // lane holds tokens 4*g + r (r = 0..3), column n of product q = expert 8*(n + 16*p) + q

@@ -117,6 +117,7 @@ struct FfnPlan {
 };
 FfnPlan plan_ffn(const pgmoe_config &cfg, int n_rows);
 size_t ffn_workspace_bytes(const pgmoe_config &cfg);
+const char *ffn_kernel_name(const pgmoe_config &cfg, int n_rows);
 
 // Kernel launchers (each validates nothing: callers did).  All asynchronous on `s`.
 int launch_gate(pgmoe_ctx *ctx, const void *x, const void *w, const float *bias, int T, int32_t *idx,
