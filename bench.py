@@ -345,7 +345,8 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
             del stk, bufs
         out["pregate_distance"] = dist
     if with_cpu:
-        sample = cpu_steps or max(1, min(K, int(round(600.0 / (T * L * k)))))
+        # about 10 s of oracle time (12.6 ms per batch-1 step of the six-block stack on one core)
+        sample = cpu_steps or max(1, min(1000, int(round(4800.0 / (T * L * k)))))
         log(f"[bench] {w.name}: timing the CPU oracle on {sample} steps")
         out["cpu_baseline"] = cpu_baseline(w, sample)
     stack.close()
@@ -389,6 +390,9 @@ def main():
     ap.add_argument("--cpu-sample-steps", type=int, default=None)
     ap.add_argument("--trace-steps", type=int, default=8)
     ap.add_argument("--host-threads", type=int, default=16)
+    ap.add_argument("--main-only", action="store_true",
+                    help="only the timed passes of --workload (no GPU-only, cache, comparison-system or distance passes): "
+                         "what the rocprofv3 summaries under profiles/ are taken from")
     ap.add_argument("--sweep-k", action="store_true",
                     help="add the activated-expert sweep (top-1..64 on the Switch-Base-64 shape, four systems)")
     args = ap.parse_args()
@@ -398,8 +402,12 @@ def main():
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
-    out = run_workload(args.workload, args.steps, args.warmup, args.host_threads, not args.no_cpu_baseline,
-                       args.cpu_sample_steps, args.trace_steps, systems=True)
+    if args.main_only:
+        out = run_workload(args.workload, args.steps, args.warmup, args.host_threads, not args.no_cpu_baseline,
+                           args.cpu_sample_steps, args.trace_steps, gpu_only=False, systems=False, cache_frac=0.0)
+    else:
+        out = run_workload(args.workload, args.steps, args.warmup, args.host_threads, not args.no_cpu_baseline,
+                           args.cpu_sample_steps, args.trace_steps, systems=True)
     out["measured_peaks"] = measured_peaks()
     others = [n for n in args.also.split(",") if n and n != args.workload]
     if args.all:
