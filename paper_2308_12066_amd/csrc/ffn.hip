@@ -29,6 +29,7 @@ namespace pgmoe {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) bf16x8 global_bf16x8;  // a load through this is a global_load, never flat
 
 // ------------------------------------------------------------------------------------------
 // Which (expert, row range, slot) does chunk number `chunk` cover?  Chunks are numbered expert
@@ -79,6 +80,18 @@ __device__ inline ChunkInfo find_chunk(const int32_t *__restrict__ offsets, int 
     return ci;
 }
 
+// Number of chunks of rows_per_chunk rows over all experts (the same count on every lane).
+__device__ inline int count_chunks(const int32_t *__restrict__ offsets, int E, int rows_per_chunk) {
+    const int lane = threadIdx.x & 63;
+    int total = 0;
+    for (int q = 0; q * 64 < E; ++q) {
+        const int e = q * 64 + lane;
+        const int n = e < E ? offsets[e + 1] - offsets[e] : 0;
+        total += __shfl(wave_incl_scan((n + rows_per_chunk - 1) / rows_per_chunk, lane), 63);
+    }
+    return total;
+}
+
 // ------------------------------------------------------------------------------------------
 // Workgroup barrier that orders LDS traffic only: global loads already in flight (the weight
 // prefetch ring) stay in flight across it.
@@ -119,13 +132,16 @@ __global__ __launch_bounds__(NW * 64) void ffn_fused_kernel(
                              : w_base + (size_t)(slot_by_rank ? ci.slot : ci.expert) * w_stride;
     const bool no_weights = table ? wexp == nullptr : (slot_by_rank && ci.slot >= n_slots);  // no slot: rows are zeroed
 
-    const bf16x8 *w1 = reinterpret_cast<const bf16x8 *>(wexp) + lane;
-    const bf16x8 *w2 = reinterpret_cast<const bf16x8 *>(wexp + (size_t)d * f * 2) + lane;
+    // weights are addressed as global memory explicitly: the blob's address may come out of the
+    // cache's pointer table, and a load the compiler cannot prove global becomes a flat load, which
+    // also counts on the LDS wait counter and would drain the prefetch ring at every LDS read
+    const global_bf16x8 *w1 = (const global_bf16x8 *)wexp + lane;
+    const global_bf16x8 *w2 = (const global_bf16x8 *)(wexp + (size_t)d * f * 2) + lane;
     const int n_sub = no_weights ? 0 : f_range / SUB;
     const int fs0 = blockIdx.y * f_range;
 
     // tile i (0 <= i < NT, compile-time after unrolling) of sub-slab s
-    auto tile_ptr = [&](int s, int i) -> const bf16x8 * {
+    auto tile_ptr = [&](int s, int i) -> const global_bf16x8 * {
         const int fs = fs0 + s * SUB;
         if (i < NT_A) return w1 + (((size_t)((fs >> 4) + wave) * KT + i) << 6);
         const int j = i - NT_A, kb = j / NTB, a = j - kb * NTB;
@@ -266,8 +282,8 @@ __global__ __launch_bounds__(256) void ffn_decode_kernel(
 
     bf16x8 ta[NA], tb[NB];
     if (!no_weights) {
-        const bf16x8 *w1 = reinterpret_cast<const bf16x8 *>(wexp) + (((size_t)((fs >> 4) + cw) * KT) << 6) + lane;
-        const bf16x8 *w2 = reinterpret_cast<const bf16x8 *>(wexp + (size_t)d * f * 2) +
+        const global_bf16x8 *w1 = (const global_bf16x8 *)wexp + (((size_t)((fs >> 4) + cw) * KT) << 6) + lane;
+        const global_bf16x8 *w2 = (const global_bf16x8 *)(wexp + (size_t)d * f * 2) +
                            (((size_t)(fs >> 5) * NTD + wave * NB) << 6) + lane;
 #pragma unroll
         for (int i = 0; i < NA; ++i) ta[i] = w1[(size_t)(ks + 2 * i) << 6];
@@ -327,6 +343,166 @@ __global__ __launch_bounds__(256) void ffn_decode_kernel(
     for (int a = 0; a < NB; ++a) {
         const floatx4 y = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tb[a], hfrag, floatx4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
         if (tok < ci.nrows) *reinterpret_cast<floatx4 *>(dst + a * 16) = y;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Many rows per expert (hundreds): the launch is bound by the matrix cores, not by HBM, and the
+// weights must be reused across many rows, so the two products run as two tiled GEMMs with the
+// hidden activation (bf16) parked in the workspace between them:
+//   UP   (DOWN == false)  H[rows, f] = ReLU(X[rows, d] . W1)         K = d
+//   DOWN (DOWN == true)   partial[s][rows, d] = H[rows, K-slice s] . W2   K = f / n_split
+// Workgroup tile: 256 rows x 128 output columns, four wavefronts as 2 x 2, each 128 rows x 64
+// columns = 8 x 4 accumulator tiles (32 matrix-core products per 12 LDS operand reads per
+// k-tile).  Both operands go through LDS in operand order, 64 k per stage; the global loads of
+// the next GEMM_RING stages are in flight (in registers) while the current one is multiplied.
+constexpr int GEMM_ROWS = 256, GEMM_COLS = 128, GEMM_KSTEP = 64, GEMM_RING = 2;
+
+template <bool DOWN>
+__global__ __launch_bounds__(256) void ffn_gemm_kernel(
+    const __bf16 *__restrict__ a_rows, int lda, const int32_t *__restrict__ offsets, int E, int d, int f, int n_split,
+    const char *__restrict__ w_base, size_t w_stride, int slot_by_rank, int n_slots,
+    const unsigned long long *__restrict__ table, __bf16 *__restrict__ h_out, float *__restrict__ partial, int n_rows) {
+    __shared__ __attribute__((aligned(16))) bf16x8 a_lds[2 * 16 * 64];  // [k-tile][row-tile][cell]
+    __shared__ __attribute__((aligned(16))) bf16x8 w_lds[2 * 8 * 64];   // [k-tile][n-tile][cell]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wn = wave & 1, wm = wave >> 1;  // 64-column half, 128-row half
+
+    // Workgroups go to the 8 XCDs round-robin in launch order and every XCD has its own L2.
+    // The (chunk, column block) items that exist are dealt out so that each XCD works through one
+    // contiguous run of them, chunk-major: the workgroups that share a chunk's rows, and the
+    // chunks that share an expert's weights, then meet in the same L2.
+    int chunk_id, col_id;
+    {
+        const int gy = gridDim.y;
+        const int n_items = count_chunks(offsets, E, GEMM_ROWS) * gy;
+        const int lin = blockIdx.y * gridDim.x + blockIdx.x;
+        const int xcd = lin & 7, turn = lin >> 3;
+        if (turn >= (n_items >> 3) + (xcd < (n_items & 7) ? 1 : 0)) return;  // uniform over the workgroup
+        const int item = xcd * (n_items >> 3) + min(xcd, n_items & 7) + turn;
+        chunk_id = item / gy;
+        col_id = item - chunk_id * gy;
+    }
+    const ChunkInfo ci = find_chunk(offsets, E, GEMM_ROWS, chunk_id);
+    if (ci.nrows == 0) return;  // uniform over the workgroup
+    const char *wexp = table ? reinterpret_cast<const char *>(table[ci.expert])
+                             : w_base + (size_t)(slot_by_rank ? ci.slot : ci.expert) * w_stride;
+    const bool no_weights = table ? wexp == nullptr : (slot_by_rank && ci.slot >= n_slots);  // no slot: rows are zeroed
+
+    const int N = DOWN ? d : f;                  // output columns of this product
+    const int n_blocks = N / GEMM_COLS;
+    const int nb = col_id % n_blocks, split = col_id / n_blocks;
+    const int n0 = nb * GEMM_COLS;
+    const int k_len = DOWN ? f / n_split : d;
+    const int k_begin = DOWN ? split * k_len : 0;
+    // an expert without a slot reads the first blob of the pool instead (a valid address) and
+    // its rows are written as zeros below
+    const char *wsafe = no_weights ? w_base : wexp;
+    const global_bf16x8 *wmat = (const global_bf16x8 *)(DOWN ? wsafe + (size_t)d * f * 2 : wsafe) + lane;
+    const int w_kt = DOWN ? f / 32 : d / 32;     // k-tiles of the whole matrix
+    const int w_nt = N / 16;                     // n-tiles of the whole matrix
+
+    // staging: this wavefront's 8 A fragments and 4 W fragments of a 64-k stage, held in a ring
+    // of GEMM_RING stages of registers: stage s + GEMM_RING is requested when stage s has been
+    // handed to LDS, so a request has GEMM_RING stages of matrix-core work to arrive in
+    const int tok = lane & 15, g = lane >> 4;
+    bf16x8 sa[GEMM_RING][8], sw[GEMM_RING][4];
+    // A rows are fetched as whole 128-byte lines (8 lanes per row, 8 rows per load), so inside
+    // LDS the 16-byte cells of a fragment are placed by a swizzle that keeps both the row-major
+    // writes and the operand-order reads (lane = token + 16 * k-group) free of bank conflicts.
+    auto cell_of = [](int t, int kg, int kt) { return 16 * (t >> 2) + 4 * ((t & 3) ^ ((kt & 1) << 1)) + (kg ^ (t >> 2)); };
+    const int ld_row = lane >> 3, ld_kt = (lane >> 2) & 1, ld_kg = lane & 3;
+    auto request = [&](int k0, bf16x8 (&ra)[8], bf16x8 (&rw)[4]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = (wave * 8 + i) * 8 + ld_row;
+            // rows past the chunk's end read the chunk's last row (a valid address); what is
+            // computed for them is never stored.  Nothing may touch the loaded value before it
+            // goes to LDS, or the wait for it would move up to here and undo the prefetch.
+            const int rc = min(r, ci.nrows - 1);
+            ra[i] = *(const global_bf16x8 *)(a_rows + (size_t)(ci.row0 + rc) * lda + k0 + 8 * (lane & 7));
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = wave * 4 + i, kt = idx >> 3, nt = idx & 7;
+            const int gkt = (k0 >> 5) + kt, gnt = (n0 >> 4) + nt;
+            const size_t tile = DOWN ? (size_t)gkt * w_nt + gnt : (size_t)gnt * w_kt + gkt;
+            rw[i] = wmat[tile << 6];
+        }
+    };
+    // where this lane's 8 staged A cells go, and where its operand cells are read from
+    int st_cell[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = (wave * 8 + i) * 8 + ld_row;
+        st_cell[i] = (ld_kt * 16 + (r >> 4)) * 64 + cell_of(r & 15, ld_kg, ld_kt);
+    }
+    const int rd_cell0 = cell_of(tok, g, 0), rd_cell1 = cell_of(tok, g, 1);
+
+    floatx4 acc[4][8];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int m = 0; m < 8; ++m) acc[a][m] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // n_stage is a multiple of GEMM_RING (the launcher checks), and a request past the last stage
+    // re-reads the last one instead of being skipped: the loop body has no conditional around the
+    // ring registers, so the compiler never has to merge (and thereby wait for) loaded values.
+    const int n_stage = k_len / GEMM_KSTEP;
+    const int k_last = k_begin + k_len - GEMM_KSTEP;
+#pragma unroll
+    for (int r = 0; r < GEMM_RING; ++r) request(min(k_begin + r * GEMM_KSTEP, k_last), sa[r], sw[r]);
+    for (int s0 = 0; s0 < n_stage; s0 += GEMM_RING) {
+#pragma unroll
+        for (int r = 0; r < GEMM_RING; ++r) {
+            const int st = s0 + r;
+            __syncthreads();  // everyone is done reading the previous stage
+#pragma unroll
+            for (int i = 0; i < 8; ++i) a_lds[st_cell[i]] = sa[r][i];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) w_lds[(wave * 4 + i) * 64 + lane] = sw[r][i];
+            __syncthreads();
+            request(min(k_begin + (st + GEMM_RING) * GEMM_KSTEP, k_last), sa[r], sw[r]);
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) {
+                bf16x8 wf[4], af[8];
+#pragma unroll
+                for (int a = 0; a < 4; ++a) wf[a] = w_lds[(kt * 8 + wn * 4 + a) * 64 + lane];
+#pragma unroll
+                for (int m = 0; m < 8; ++m) af[m] = a_lds[(kt * 16 + wm * 8 + m) * 64 + (kt ? rd_cell1 : rd_cell0)];
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+#pragma unroll
+                    for (int m = 0; m < 8; ++m)
+                        acc[a][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[a], af[m], acc[a][m], 0, 0, 0);
+            }
+        }
+    }
+
+    // lane holds row (wm*128 + m*16 + tok), output columns n0 + wn*64 + a*16 + 4*g + {0..3}
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+        const int r = wm * 128 + m * 16 + tok;
+        if (r >= ci.nrows) continue;
+        const size_t row = (size_t)ci.row0 + r;
+        const int col = n0 + wn * 64 + 4 * g;
+        if (DOWN) {
+            float *dst = partial + ((size_t)split * n_rows + row) * d + col;
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                *reinterpret_cast<floatx4 *>(dst + a * 16) = no_weights ? floatx4{0.f, 0.f, 0.f, 0.f} : acc[a][m];
+        } else {
+            __bf16 *dst = h_out + row * f + col;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                bf16x4 o;
+                o.x = (__bf16)fmaxf(acc[a][m].x, 0.f);
+                o.y = (__bf16)fmaxf(acc[a][m].y, 0.f);
+                o.z = (__bf16)fmaxf(acc[a][m].z, 0.f);
+                o.w = (__bf16)fmaxf(acc[a][m].w, 0.f);
+                *reinterpret_cast<bf16x4 *>(dst + a * 16) = o;
+            }
+        }
     }
 }
 
@@ -485,8 +661,20 @@ static bool uses_decode_kernel(const pgmoe_config &c, const FfnPlan &p) {
     return p.mt == 1 && p.nw == 2 && p.n_partial == c.d_ff / 32 && (kt == 24 || kt == 32) && !getenv("PGMOE_FFN_NO_DECODE");
 }
 
+// The two-GEMM path pays off once an expert sees enough rows for its weights to be reused out
+// of LDS many times: at least 192 rows per expert on average.
+constexpr int GEMM_SPLIT = 4;  // K slices of the down-projection (float32 partials)
+static bool uses_gemm_kernels(const pgmoe_config &c, int n_rows) {
+    if (c.dtype != PGMOE_BF16 || getenv("PGMOE_FFN_NO_GEMM")) return false;
+    constexpr int kgroup = GEMM_KSTEP * GEMM_RING;  // the k loop runs in whole rings
+    if (c.d_model % GEMM_COLS || c.d_ff % GEMM_COLS || c.d_model % kgroup || c.d_ff % (GEMM_SPLIT * kgroup)) return false;
+    const int active = std::max(1, std::min(c.n_experts, n_rows));
+    return n_rows / active >= 192;
+}
+
 const char *ffn_kernel_name(const pgmoe_config &c, int n_rows) {
     if (c.dtype == PGMOE_F32) return "ffn_f32_hidden_kernel+ffn_f32_out_kernel";
+    if (uses_gemm_kernels(c, n_rows)) return "ffn_gemm_kernel";
     return uses_decode_kernel(c, plan_ffn(c, n_rows)) ? "ffn_decode_kernel" : "ffn_fused_kernel";
 }
 
@@ -496,7 +684,9 @@ size_t ffn_workspace_bytes(const pgmoe_config &c) {
     // worst case over every geometry plan_ffn can pick: one partial per 32-column sub-slab
     const size_t worst = (size_t)(c.d_ff / 32) * std::min<int64_t>(max_rows, 4096) * c.d_model * 4;
     const size_t big = (size_t)16 * max_rows * c.d_model * 4;
-    return ((std::max(worst, big) + 255) & ~(size_t)255);
+    // two-GEMM path: the partials of the down-projection, then the bf16 hidden activation
+    const size_t gemm = (size_t)GEMM_SPLIT * max_rows * c.d_model * 4 + (size_t)max_rows * c.d_ff * 2 + 256;
+    return ((std::max(std::max(worst, big), gemm) + 255) & ~(size_t)255);
 }
 
 // Next free event pair when FFN timing is on, else -1.
@@ -566,6 +756,38 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
                            c.n_experts, c.d_model, c.d_ff, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, (float *)y_perm);
         PG_HIP(ctx, hipGetLastError());
         if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
+        return PGMOE_OK;
+    }
+    if (uses_gemm_kernels(c, n_rows)) {
+        // hidden activation [n_rows, f] bf16 first, then GEMM_SPLIT float32 partials [n_rows, d]
+        const size_t h_bytes = ((size_t)n_rows * c.d_ff * 2 + 255) & ~(size_t)255;
+        const size_t p_bytes = (size_t)GEMM_SPLIT * n_rows * c.d_model * 4;
+        if (h_bytes + p_bytes > ffn_workspace_bytes(c))
+            return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: hidden activation and partial sums of %d rows do not fit the workspace", n_rows);
+        __bf16 *h = (__bf16 *)((char *)workspace + p_bytes);  // partials first: the combine reads them at the workspace's start
+        float *partial = (float *)workspace;
+        const int active = std::max(1, std::min(c.n_experts, n_rows));
+        const int max_chunks = active + n_rows / GEMM_ROWS;
+        const int tslot = timing_slot(ctx);
+        if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_begin[tslot], s));
+        hipLaunchKernelGGL(ffn_gemm_kernel<false>, dim3(max_chunks, c.d_ff / GEMM_COLS), dim3(256), 0, s, (const __bf16 *)x_perm,
+                           c.d_model, offsets, c.n_experts, c.d_model, c.d_ff, 1, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots,
+                           table, h, (float *)nullptr, n_rows);
+        PG_HIP(ctx, hipGetLastError());
+        hipLaunchKernelGGL(ffn_gemm_kernel<true>, dim3(max_chunks, (c.d_model / GEMM_COLS) * GEMM_SPLIT), dim3(256), 0, s,
+                           (const __bf16 *)h, c.d_ff, offsets, c.n_experts, c.d_model, c.d_ff, GEMM_SPLIT, w_base, w_stride,
+                           slot_by_rank ? 1 : 0, n_slots, table, (__bf16 *)nullptr, partial, n_rows);
+        PG_HIP(ctx, hipGetLastError());
+        if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
+        if (keep_partials) {
+            *keep_partials = GEMM_SPLIT;
+            return PGMOE_OK;
+        }
+        const size_t total4 = (size_t)n_rows * c.d_model / 4;
+        static_assert(GEMM_SPLIT > 2 && GEMM_SPLIT <= 8, "ffn_reduce_kernel<4> is what reduce_lanes() gives for this many partials");
+        hipLaunchKernelGGL(ffn_reduce_kernel<4>, dim3((unsigned)((total4 + 63) / 64)), dim3(256), 0, s, partial, GEMM_SPLIT, n_rows,
+                           c.d_model, (__bf16 *)y_perm);
+        PG_HIP(ctx, hipGetLastError());
         return PGMOE_OK;
     }
     const FfnPlan p = plan_ffn(c, n_rows);

@@ -225,6 +225,9 @@ FFN_CASES = [
     ("bf16", 768, 3072, 5, [17, 0, 0, 0, 2]),
     ("bf16", 768, 3072, 4, [4, 0, 3, 0]),
     ("bf16", 1024, 4096, 3, [1, 0, 2]),
+    # hundreds of rows per expert: the two tiled GEMMs (ragged 256-row chunks, an idle expert, a 5-row expert)
+    ("bf16", 768, 3072, 2, [300, 217]),
+    ("bf16", 256, 512, 3, [0, 700, 5]),
 ]
 
 
@@ -349,7 +352,7 @@ def test_cfg1_tiny_f32_stack_all_tokens(hx):
 
 @pytest.mark.parametrize("name,blocks,steps,sample,fetch", [
     ("cfg2", 6, 6, None, "pull"), ("cfg2", 6, 4, None, "memcpy"), ("cfg3", 6, 3, None, "pull"),
-    ("cfg4", 2, 1, 192, "-"), ("cfg4_offloaded", 2, 1, 64, "pull"), ("cfg5", 3, 2, None, "pull"),
+    ("cfg4", 2, 1, 192, "-"), ("base8_prefill", 2, 1, 96, "-"), ("cfg4_offloaded", 2, 1, 64, "pull"), ("cfg5", 3, 2, None, "pull"),
     ("cfg5_top2", 3, 2, None, "pull"), ("cfg5_top2", 3, 2, None, "memcpy"),
     ("sweep64_k4", 2, 2, None, "pull"), ("sweep64_k16", 2, 1, None, "memcpy"), ("sweep64_k64", 2, 2, None, "pull"),
 ])
