@@ -356,14 +356,16 @@ __global__ __launch_bounds__(256) void ffn_decode_kernel(
 // columns = 8 x 4 accumulator tiles (32 matrix-core products per 12 LDS operand reads per
 // k-tile).  Both operands go through LDS in operand order, 64 k per stage; the global loads of
 // the next GEMM_RING stages are in flight (in registers) while the current one is multiplied.
-constexpr int GEMM_ROWS = 256, GEMM_COLS = 128, GEMM_KSTEP = 64, GEMM_RING = 2;
+constexpr int GEMM_COLS = 128, GEMM_KSTEP = 64, GEMM_RING = 2;
 
-template <bool DOWN>
+// WMT: 16-row tiles per wavefront; the workgroup tile is 32 * WMT rows (256 or 128) by 128 columns.
+template <bool DOWN, int WMT>
 __global__ __launch_bounds__(256) void ffn_gemm_kernel(
     const __bf16 *__restrict__ a_rows, int lda, const int32_t *__restrict__ offsets, int E, int d, int f, int n_split,
     const char *__restrict__ w_base, size_t w_stride, int slot_by_rank, int n_slots,
     const unsigned long long *__restrict__ table, __bf16 *__restrict__ h_out, float *__restrict__ partial, int n_rows) {
-    __shared__ __attribute__((aligned(16))) bf16x8 a_lds[2 * 16 * 64];  // [k-tile][row-tile][cell]
+    constexpr int ROWS = 32 * WMT, RT = 2 * WMT, NA = ROWS / 32;  // rows, row tiles, A loads per wavefront and stage
+    __shared__ __attribute__((aligned(16))) bf16x8 a_lds[2 * RT * 64];  // [k-tile][row-tile][cell]
     __shared__ __attribute__((aligned(16))) bf16x8 w_lds[2 * 8 * 64];   // [k-tile][n-tile][cell]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = wave & 1, wm = wave >> 1;  // 64-column half, 128-row half
@@ -375,7 +377,7 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
     int chunk_id, col_id;
     {
         const int gy = gridDim.y;
-        const int n_items = count_chunks(offsets, E, GEMM_ROWS) * gy;
+        const int n_items = count_chunks(offsets, E, ROWS) * gy;
         const int lin = blockIdx.y * gridDim.x + blockIdx.x;
         const int xcd = lin & 7, turn = lin >> 3;
         if (turn >= (n_items >> 3) + (xcd < (n_items & 7) ? 1 : 0)) return;  // uniform over the workgroup
@@ -383,7 +385,7 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
         chunk_id = item / gy;
         col_id = item - chunk_id * gy;
     }
-    const ChunkInfo ci = find_chunk(offsets, E, GEMM_ROWS, chunk_id);
+    const ChunkInfo ci = find_chunk(offsets, E, ROWS, chunk_id);
     if (ci.nrows == 0) return;  // uniform over the workgroup
     const char *wexp = table ? reinterpret_cast<const char *>(table[ci.expert])
                              : w_base + (size_t)(slot_by_rank ? ci.slot : ci.expert) * w_stride;
@@ -406,16 +408,16 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
     // of GEMM_RING stages of registers: stage s + GEMM_RING is requested when stage s has been
     // handed to LDS, so a request has GEMM_RING stages of matrix-core work to arrive in
     const int tok = lane & 15, g = lane >> 4;
-    bf16x8 sa[GEMM_RING][8], sw[GEMM_RING][4];
+    bf16x8 sa[GEMM_RING][NA], sw[GEMM_RING][4];
     // A rows are fetched as whole 128-byte lines (8 lanes per row, 8 rows per load), so inside
     // LDS the 16-byte cells of a fragment are placed by a swizzle that keeps both the row-major
     // writes and the operand-order reads (lane = token + 16 * k-group) free of bank conflicts.
     auto cell_of = [](int t, int kg, int kt) { return 16 * (t >> 2) + 4 * ((t & 3) ^ ((kt & 1) << 1)) + (kg ^ (t >> 2)); };
     const int ld_row = lane >> 3, ld_kt = (lane >> 2) & 1, ld_kg = lane & 3;
-    auto request = [&](int k0, bf16x8 (&ra)[8], bf16x8 (&rw)[4]) {
+    auto request = [&](int k0, bf16x8 (&ra)[NA], bf16x8 (&rw)[4]) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int r = (wave * 8 + i) * 8 + ld_row;
+        for (int i = 0; i < NA; ++i) {
+            const int r = (wave * NA + i) * 8 + ld_row;
             // rows past the chunk's end read the chunk's last row (a valid address); what is
             // computed for them is never stored.  Nothing may touch the loaded value before it
             // goes to LDS, or the wait for it would move up to here and undo the prefetch.
@@ -431,19 +433,19 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
         }
     };
     // where this lane's 8 staged A cells go, and where its operand cells are read from
-    int st_cell[8];
+    int st_cell[NA];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int r = (wave * 8 + i) * 8 + ld_row;
-        st_cell[i] = (ld_kt * 16 + (r >> 4)) * 64 + cell_of(r & 15, ld_kg, ld_kt);
+    for (int i = 0; i < NA; ++i) {
+        const int r = (wave * NA + i) * 8 + ld_row;
+        st_cell[i] = (ld_kt * RT + (r >> 4)) * 64 + cell_of(r & 15, ld_kg, ld_kt);
     }
     const int rd_cell0 = cell_of(tok, g, 0), rd_cell1 = cell_of(tok, g, 1);
 
-    floatx4 acc[4][8];
+    floatx4 acc[4][WMT];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int m = 0; m < 8; ++m) acc[a][m] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int m = 0; m < WMT; ++m) acc[a][m] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     // n_stage is a multiple of GEMM_RING (the launcher checks), and a request past the last stage
     // re-reads the last one instead of being skipped: the loop body has no conditional around the
@@ -458,22 +460,22 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
             const int st = s0 + r;
             __syncthreads();  // everyone is done reading the previous stage
 #pragma unroll
-            for (int i = 0; i < 8; ++i) a_lds[st_cell[i]] = sa[r][i];
+            for (int i = 0; i < NA; ++i) a_lds[st_cell[i]] = sa[r][i];
 #pragma unroll
             for (int i = 0; i < 4; ++i) w_lds[(wave * 4 + i) * 64 + lane] = sw[r][i];
             __syncthreads();
             request(min(k_begin + (st + GEMM_RING) * GEMM_KSTEP, k_last), sa[r], sw[r]);
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
-                bf16x8 wf[4], af[8];
+                bf16x8 wf[4], af[WMT];
 #pragma unroll
                 for (int a = 0; a < 4; ++a) wf[a] = w_lds[(kt * 8 + wn * 4 + a) * 64 + lane];
 #pragma unroll
-                for (int m = 0; m < 8; ++m) af[m] = a_lds[(kt * 16 + wm * 8 + m) * 64 + (kt ? rd_cell1 : rd_cell0)];
+                for (int m = 0; m < WMT; ++m) af[m] = a_lds[(kt * RT + wm * WMT + m) * 64 + (kt ? rd_cell1 : rd_cell0)];
 #pragma unroll
                 for (int a = 0; a < 4; ++a)
 #pragma unroll
-                    for (int m = 0; m < 8; ++m)
+                    for (int m = 0; m < WMT; ++m)
                         acc[a][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[a], af[m], acc[a][m], 0, 0, 0);
             }
         }
@@ -481,8 +483,8 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
 
     // lane holds row (wm*128 + m*16 + tok), output columns n0 + wn*64 + a*16 + 4*g + {0..3}
 #pragma unroll
-    for (int m = 0; m < 8; ++m) {
-        const int r = wm * 128 + m * 16 + tok;
+    for (int m = 0; m < WMT; ++m) {
+        const int r = wm * 16 * WMT + m * 16 + tok;
         if (r >= ci.nrows) continue;
         const size_t row = (size_t)ci.row0 + r;
         const int col = n0 + wn * 64 + 4 * g;
@@ -767,17 +769,21 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
         __bf16 *h = (__bf16 *)((char *)workspace + p_bytes);  // partials first: the combine reads them at the workspace's start
         float *partial = (float *)workspace;
         const int active = std::max(1, std::min(c.n_experts, n_rows));
-        const int max_chunks = active + n_rows / GEMM_ROWS;
+        const int wmt = env_int("PGMOE_GEMM_WMT", 4);   // 128-row tiles (3 workgroups per CU) or 256-row tiles
+        const int max_chunks = active + n_rows / (32 * wmt);
         const int tslot = timing_slot(ctx);
         if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_begin[tslot], s));
-        hipLaunchKernelGGL(ffn_gemm_kernel<false>, dim3(max_chunks, c.d_ff / GEMM_COLS), dim3(256), 0, s, (const __bf16 *)x_perm,
-                           c.d_model, offsets, c.n_experts, c.d_model, c.d_ff, 1, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots,
-                           table, h, (float *)nullptr, n_rows);
+        const dim3 grid_up(max_chunks, c.d_ff / GEMM_COLS), grid_down(max_chunks, (c.d_model / GEMM_COLS) * GEMM_SPLIT);
+#define PG_GEMM(DOWN_, WMT_, GRID_, A_, LDA_, SPLIT_, H_, P_)                                                                  \
+    hipLaunchKernelGGL((ffn_gemm_kernel<DOWN_, WMT_>), GRID_, dim3(256), 0, s, A_, LDA_, offsets, c.n_experts, c.d_model, c.d_ff, \
+                       SPLIT_, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, H_, P_, n_rows)
+        if (wmt == 8) PG_GEMM(false, 8, grid_up, (const __bf16 *)x_perm, c.d_model, 1, h, (float *)nullptr);
+        else PG_GEMM(false, 4, grid_up, (const __bf16 *)x_perm, c.d_model, 1, h, (float *)nullptr);
         PG_HIP(ctx, hipGetLastError());
-        hipLaunchKernelGGL(ffn_gemm_kernel<true>, dim3(max_chunks, (c.d_model / GEMM_COLS) * GEMM_SPLIT), dim3(256), 0, s,
-                           (const __bf16 *)h, c.d_ff, offsets, c.n_experts, c.d_model, c.d_ff, GEMM_SPLIT, w_base, w_stride,
-                           slot_by_rank ? 1 : 0, n_slots, table, (__bf16 *)nullptr, partial, n_rows);
+        if (wmt == 8) PG_GEMM(true, 8, grid_down, (const __bf16 *)h, c.d_ff, GEMM_SPLIT, (__bf16 *)nullptr, partial);
+        else PG_GEMM(true, 4, grid_down, (const __bf16 *)h, c.d_ff, GEMM_SPLIT, (__bf16 *)nullptr, partial);
         PG_HIP(ctx, hipGetLastError());
+#undef PG_GEMM
         if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
         if (keep_partials) {
             *keep_partials = GEMM_SPLIT;
