@@ -28,26 +28,31 @@ F32, BF16, F64 = 0, 1, 2
 _lib = None
 
 
+def bind(path: str):
+    """Load an oracle library and declare its entry points (lib() does this for the built one;
+    the mutation tests do it for deliberately broken copies)."""
+    L = ctypes.CDLL(path)
+    dp = ctypes.POINTER(ctypes.c_double)
+    ip = ctypes.POINTER(ctypes.c_int32)
+    vpp = ctypes.POINTER(ctypes.c_void_p)
+    ci = ctypes.c_int
+    L.pgo_max_threads.restype = ci
+    L.pgo_gate_logits.argtypes = [dp, dp, dp, ci, ci, ci, dp]
+    L.pgo_softmax.argtypes = [dp, ci, ci, dp]
+    L.pgo_topk.argtypes = [dp, ci, ci, ci, ip, dp, ip]
+    L.pgo_route.argtypes = [ip, ci, ci, ci, ip, ip, ip, ip, ip]
+    L.pgo_ffn_rows.argtypes = [dp, ci, ci, ci, ctypes.c_void_p, ctypes.c_void_p, ci, dp, ci]
+    L.pgo_block.argtypes = [dp, dp, ip, ci, ci, ci, ci, ci, vpp, vpp, ci, dp, ci]
+    L.pgo_block.restype = ci
+    for f in (L.pgo_gate_logits, L.pgo_softmax, L.pgo_topk, L.pgo_route, L.pgo_ffn_rows):
+        f.restype = None
+    return L
+
+
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
-        L = ctypes.CDLL(path)
-        dp = ctypes.POINTER(ctypes.c_double)
-        ip = ctypes.POINTER(ctypes.c_int32)
-        vpp = ctypes.POINTER(ctypes.c_void_p)
-        ci = ctypes.c_int
-        L.pgo_max_threads.restype = ci
-        L.pgo_gate_logits.argtypes = [dp, dp, dp, ci, ci, ci, dp]
-        L.pgo_softmax.argtypes = [dp, ci, ci, dp]
-        L.pgo_topk.argtypes = [dp, ci, ci, ci, ip, dp, ip]
-        L.pgo_route.argtypes = [ip, ci, ci, ci, ip, ip, ip, ip, ip]
-        L.pgo_ffn_rows.argtypes = [dp, ci, ci, ci, ctypes.c_void_p, ctypes.c_void_p, ci, dp, ci]
-        L.pgo_block.argtypes = [dp, dp, ip, ci, ci, ci, ci, ci, vpp, vpp, ci, dp, ci]
-        L.pgo_block.restype = ci
-        for f in (L.pgo_gate_logits, L.pgo_softmax, L.pgo_topk, L.pgo_route, L.pgo_ffn_rows):
-            f.restype = None
-        _lib = L
+        _lib = bind(_build.build(force=False))
     return _lib
 
 
