@@ -101,7 +101,7 @@ def pmc_traffic(workload_name):
 
 
 def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gpu_only=True, systems=False,
-                 cache_frac=0.2, store=None):
+                 cache_frac=0.2, store=None, graphs=False):
     import numpy as np
     import torch
 
@@ -156,6 +156,33 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
 
     dt, dt_events, n_timed, ffn_ms, overhead_us = two_passes(stack, step_bufs)
 
+    def graph_replay(stk, buf, x_buf):
+        """One step captured into a HIP graph (pgmoe_stack_step only enqueues) and replayed K times,
+        each time after copying that step's input into the captured input buffer: what a serving
+        loop that re-uses its buffers runs.  Same work per step as the eager loop (gates,
+        migration, FFNs, fresh routing per step)."""
+        g = torch.cuda.CUDAGraph()
+        saved = x_buf.clone()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=stk.compute):
+            stk.ctx.stack_step(buf, T, stk.compute, stk.copy)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stk.compute):
+            for s in range(Wm):
+                x_buf.copy_(x_all[(s + 1) % n_in, 0], non_blocking=True)
+                g.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for s in range(K):
+                x_buf.copy_(x_all[(s + 1) % n_in, 0], non_blocking=True)
+                g.replay()
+            torch.cuda.synchronize()
+            dtg = time.perf_counter() - t0
+        del g
+        x_buf.copy_(saved)          # step 0's own input back in place for the later passes
+        torch.cuda.synchronize()
+        return {"tokens_per_s": T * K / dtg, "ms_per_step": 1e3 * dtg / K}
+
     # algorithmic bytes of the FFN launches: weights of the distinct experts each launch touches
     # plus its activation rows in and out
     idx_host = idx_log.cpu().numpy()
@@ -206,6 +233,8 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         out["roofline"].update({"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                 "frac": tf / MFMA_BF16_PEAK_TFLOPS, "flops_per_launch": flops,
                                 "hbm_achieved_GBps": ffn_gbps, "hbm_frac": ffn_gbps / HBM_PEAK_GBPS})
+    if graphs:
+        out["graph_replay"] = graph_replay(stack, step_bufs[0], x_all[0, 0])
     if w.offloaded and trace_steps > 0:
         # pass 3: instrumented steps for the overlap figures (per-block events on both streams)
         stack.ctx.trace(True)
@@ -255,6 +284,8 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
                            "ffn_avg_launch_us": us2, "ffn_achieved_GBps": per_launch / (us2 * 1e-6) / 1e9,
                            "ffn_frac_of_hbm_peak": per_launch / (us2 * 1e-6) / 1e9 / HBM_PEAK_GBPS,
                            "note": "same workload and routing with all experts resident in HBM (no migration)"}
+        if graphs:
+            out["gpu_only"]["graph_replay"] = graph_replay(stack2, bufs2[0], x_all[0, 0])
         stack2.close()
         del stack2, bufs2
     if w.offloaded and cache_frac > 0:
@@ -418,7 +449,7 @@ def main():
                            args.cpu_sample_steps, args.trace_steps, gpu_only=False, systems=False, cache_frac=0.0)
     else:
         out = run_workload(args.workload, args.steps, args.warmup, args.host_threads, not args.no_cpu_baseline,
-                           args.cpu_sample_steps, args.trace_steps, systems=True)
+                           args.cpu_sample_steps, args.trace_steps, systems=True, graphs=True)
     out["measured_peaks"] = measured_peaks()
     others = [n for n in args.also.split(",") if n and n != args.workload]
     if args.all:

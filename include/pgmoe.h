@@ -244,6 +244,12 @@ int pgmoe_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, con
  *   block L-1 : no gate.
  * gate_w[0] / gate_b[0] is block 0's conventional gate, gate_w[g] / gate_b[g] for g >= 1 the
  * pre-gate that sits in block g-1 (routes block g).
+ * The call only enqueues work (no host wait, no allocation, no memset) when the migration runs
+ * in pull mode without an expert cache and neither tracing nor fetch timing is on, so it may be
+ * captured into a HIP graph on compute_stream and replayed (the copy streams join the capture
+ * through the call's own events and are joined back before it returns).  Not capturable:
+ * PGMOE_FLAG_FETCH_MEMCPY (the host waits for the routing) and cache_slots > 0 (the cache
+ * bookkeeping alternates between two device copies from call to call).
  * With pregate_distance N > 1 the gate that routes block g is evaluated on x_{max(0, g-N)}:
  * block 0 runs the gates of blocks 0..N on x_0 and queues their fetches back to back, block
  * i >= 1 runs the gate of block i+N; the last N blocks run none.  Arrays of pointers are host arrays of

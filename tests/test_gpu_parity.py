@@ -420,6 +420,52 @@ def test_pregate_distance_routes_from_the_earlier_state_and_keeps_more_generatio
     stack.close()
 
 
+@pytest.mark.parametrize("offloaded", [False, True])
+def test_stack_step_replays_from_a_captured_graph(hx, offloaded):
+    """pgmoe_stack_step only enqueues (pull-mode migration, no host wait, no memset), so a caller
+    can capture one step into a HIP graph and replay it: every replay, with the program's own
+    eager work and synchronisations in between, must give exactly what the eager step gives."""
+    H, B = hx
+    w = small_workload("bf16", 6, 128, 256, 8, 2, L=4, offloaded=offloaded, index=53)
+    say(f"graph replay: offloaded={offloaded}")
+    stack, gates, cache = make_stack(H, w, weight_scale=4.0)
+    xs_in = [H.to_device(W.step_input(w, s), w.dtype) for s in range(4)]
+    eager = []
+    for x in xs_in:                                  # eager results (and warm-up of every kernel)
+        stack.x_states[0].copy_(x)
+        torch.cuda.synchronize()
+        stack.step()
+        torch.cuda.synchronize()
+        eager.append((stack.x_states.clone(), stack.topk_idx.clone(), stack.topk_prob.clone(), stack.row_of.clone()))
+    graph = torch.cuda.CUDAGraph()
+    stack.x_states[0].copy_(xs_in[0])
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=stack.compute):
+        stack.step()
+    torch.cuda.synchronize()
+    for rep in range(2):
+        for s, x in enumerate(xs_in):
+            stack.x_states[0].copy_(x)
+            stack.x_states[1:].zero_()              # eager work between replays
+            stack.topk_idx.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            ex, ei, ep, er = eager[s]
+            assert torch.equal(stack.topk_idx, ei) and torch.equal(stack.row_of, er), f"replay {rep}/{s}: routing"
+            assert torch.equal(stack.topk_prob, ep)
+            assert torch.equal(stack.x_states.view(torch.int16), ex.view(torch.int16)), f"replay {rep}/{s}: hidden states"
+    # and the eager path still works after the capture
+    stack.x_states[0].copy_(xs_in[1])
+    torch.cuda.synchronize()
+    stack.step()
+    torch.cuda.synchronize()
+    assert torch.equal(stack.x_states.view(torch.int16), eager[1][0].view(torch.int16))
+    assert stack.ctx.device_flags() == 0
+    del graph
+    stack.close()
+
+
 # ------------------------------------------------------------------------------ migration engine
 def _device_bytes(addr, nbytes):
     """Copy nbytes from a raw device address to host (plumbing: hipMemcpy through ctypes)."""
