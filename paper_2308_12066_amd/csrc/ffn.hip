@@ -1,7 +1,11 @@
 // Expert execution (Sec. II-B: every activated expert, a dense FFN, processes the tokens
 // routed to it):  y_perm[rows of e] = ReLU(x_perm[rows of e] . W1_e) . W2_e.
 //
-// bf16 path - one fused kernel, weights streamed from HBM exactly once per 16*MT-row chunk:
+// bf16 path - three kernels, picked from the shape of the launch alone (plan_ffn and friends):
+//   ffn_fused_kernel   the general, HBM-bound case (described next);
+//   ffn_decode_kernel  a handful of active experts with <= 16 rows each (batch-1 decode);
+//   ffn_gemm_kernel    hundreds of rows per expert (bound by the matrix cores): two tiled GEMMs.
+// The fused kernel streams the weights from HBM exactly once per 16*MT-row chunk:
 //   workgroup = (chunk of <= 16*MT rows of one expert) x (a range of d_ff columns)
 //   = (blockIdx.x, blockIdx.y).
 //   It keeps the chunk's activations in LDS, already in matrix-core operand order, and walks
@@ -777,7 +781,7 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
         __bf16 *h = (__bf16 *)((char *)workspace + p_bytes);  // partials first: the combine reads them at the workspace's start
         float *partial = (float *)workspace;
         const int active = std::max(1, std::min(c.n_experts, n_rows));
-        const int wmt = env_int("PGMOE_GEMM_WMT", 4);   // 128-row tiles (3 workgroups per CU) or 256-row tiles
+        const int wmt = env_int("PGMOE_GEMM_WMT", 4);   // 128-row tiles (two workgroups per CU); 8 = 256-row tiles
         const int max_chunks = active + n_rows / (32 * wmt);
         const int tslot = timing_slot(ctx);
         if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_begin[tslot], s));

@@ -2,12 +2,15 @@
 // (Sec. II-B: the gate gives every expert a probability per token and the best ones are
 // activated; Sec. IV-B: the same function, placed in block N, routes block N+1).
 //
-// One workgroup handles a few tokens.  The token rows are staged in LDS as float32 in chunks of
-// GATE_DC features; the threads split W by expert columns and feature rows, accumulate in
-// float32 and fold their partial sums in a fixed order (bit-reproducible); then one wavefront
-// per token does the softmax and k rounds of arg-max with shuffles.  Two kernels: a vectorised
-// one for power-of-two expert counts (every configuration of the paper) and a scalar one for
-// any other E.
+// Three kernels share one softmax / top-k routine (16 lanes per token, k rounds of arg-max with
+// shuffles, ties to the lowest index, NaN ranks as -infinity and raises a flag):
+//   gate_topk_mfma_kernel  bf16, E a multiple of 8: logits on the matrix cores, 16 tokens per
+//                          workgroup, W transposed in registers (no LDS staging on the way in);
+//   gate_topk_vec_kernel   f32 (and bf16 when the matrix-core kernel does not apply) for
+//                          power-of-two E: token rows staged in LDS as float32, threads split W
+//                          by expert columns and feature rows and fold their partial sums in a
+//                          fixed order (bit-reproducible);
+//   gate_topk_kernel       the scalar version of that for any other E.
 #include <cstdlib>
 
 #include "pgmoe_internal.h"
