@@ -191,6 +191,7 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
         if (rc == PGMOE_OK) H(hipMemset(c->dev_flags, 0, flag_bytes), "hipMemset(flags)");
         c->dev_unique = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(c->dev_flags) + 64);
         size_t n_idx = (size_t)cfg->max_tokens * cfg->top_k;
+        if (rc == PGMOE_OK) H(hipMalloc((void **)&c->dev_src_row, n_idx * sizeof(int32_t)), "hipMalloc(src_row)");
         if (rc == PGMOE_OK) H(hipHostMalloc((void **)&c->idx_staging, n_idx * sizeof(int32_t), hipHostMallocDefault), "hipHostMalloc(idx staging)");
         if (rc == PGMOE_OK) H(hipEventCreateWithFlags(&c->idx_ready, hipEventDisableTiming), "hipEventCreate");
         if (rc == PGMOE_OK) H(hipStreamCreateWithFlags(&c->copy2, hipStreamNonBlocking), "hipStreamCreate");
@@ -227,6 +228,7 @@ int pgmoe_destroy(pgmoe_ctx *c) {
         if (c->cache_stats) (void)hipFree(c->cache_stats);
         delete[] c->cache_parity;
         if (c->dev_flags) (void)hipFree(c->dev_flags);
+        if (c->dev_src_row) (void)hipFree(c->dev_src_row);
         if (c->idx_staging) (void)hipHostFree(c->idx_staging);
         if (c->idx_ready) (void)hipEventDestroy(c->idx_ready);
         if (c->copy2) (void)hipStreamDestroy(c->copy2);

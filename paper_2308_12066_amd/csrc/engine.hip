@@ -345,7 +345,8 @@ int pgmoe_slot_address(pgmoe_ctx *ctx, int block, int slot, void **dev_out) {
 // pgmoe_expert_ffn with the option to leave the float32 partial sums unreduced in the workspace
 // (keep_partials != NULL; see launch_ffn), which pgmoe_stack_step feeds to the fused combine.
 static int expert_ffn_impl(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_t *expert_offsets, int n_rows,
-                           void *y_perm, void *workspace, void *stream, int *keep_partials) {
+                           void *y_perm, void *workspace, void *stream, int *keep_partials,
+                           const int32_t *src_row = nullptr) {  // src_row: x_perm holds the un-grouped rows (see launch_ffn)
     const char *fn = "pgmoe_expert_ffn";
     if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
     int rc = check_block(ctx, fn, block);
@@ -360,7 +361,8 @@ static int expert_ffn_impl(pgmoe_ctx *ctx, int block, const void *x_perm, const 
     hipStream_t s = (hipStream_t)stream;
     if (ctx->store_mode == STORE_RESIDENT)
         return launch_ffn(ctx, ctx->store_base + (size_t)block * ctx->block_stride, ctx->expert_stride, false,
-                          ctx->cfg.n_experts, x_perm, expert_offsets, n_rows, y_perm, workspace, s, keep_partials);
+                          ctx->cfg.n_experts, x_perm, expert_offsets, n_rows, y_perm, workspace, s, keep_partials, nullptr,
+                          src_row);
     const int gen = block % ctx->n_gen;
     if (ctx->fetched_block[gen] != block)
         return fail(ctx, PGMOE_ESTATE, "%s: block %d was not fetched (generation holds block %d)", fn, block, ctx->fetched_block[gen]);
@@ -370,7 +372,7 @@ static int expert_ffn_impl(pgmoe_ctx *ctx, int block, const void *x_perm, const 
     // a generation filled by pgmoe_fetch_all_experts is indexed by expert id, else by rank
     rc = launch_ffn(ctx, ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes, ctx->expert_bytes, !ctx->gen_all[gen],
                     ctx->slots, x_perm, expert_offsets, n_rows, y_perm, workspace, s, keep_partials,
-                    ctx->gen_table[gen] ? ctx->dev_table + (size_t)block * PGMOE_MAX_EXPERTS : nullptr);
+                    ctx->gen_table[gen] ? ctx->dev_table + (size_t)block * PGMOE_MAX_EXPERTS : nullptr, src_row);
     if (rc) return rc;
     ctx->ffn_recorded[gen] = true;
     ctx->ffn_stream[gen] = s;
@@ -380,6 +382,23 @@ static int expert_ffn_impl(pgmoe_ctx *ctx, int block, const void *x_perm, const 
 int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_t *expert_offsets, int n_rows,
                      void *y_perm, void *workspace, void *stream) {
     return expert_ffn_impl(ctx, block, x_perm, expert_offsets, n_rows, y_perm, workspace, stream, nullptr);
+}
+
+// Token grouping and expert FFN of one block inside pgmoe_stack_step.  bf16: only the integer
+// half of the grouping runs (offsets, row_of and the inverse map grouped row -> token); the FFN
+// kernels read their rows of x through that map, so the gather kernel and the x_perm round trip
+// are skipped (same values, hence the same results as pgmoe_permute + pgmoe_expert_ffn).
+static int group_and_run_experts(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int block, int T, const void *x,
+                                 const int32_t *idx, int32_t *row_of, int32_t *offs, void *stream, int *n_partial) {
+    const int nk = T * ctx->cfg.top_k;
+    if (ctx->cfg.dtype != PGMOE_BF16) {
+        int rc = pgmoe_permute(ctx, x, idx, T, io->x_perm, row_of, offs, stream);
+        if (rc) return rc;
+        return expert_ffn_impl(ctx, block, io->x_perm, offs, nk, io->y_perm, io->workspace, stream, n_partial);
+    }
+    int rc = launch_route(ctx, idx, T, row_of, offs, ctx->dev_src_row, (hipStream_t)stream);
+    if (rc) return rc;
+    return expert_ffn_impl(ctx, block, x, offs, nk, io->y_perm, io->workspace, stream, n_partial, ctx->dev_src_row);
 }
 
 int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *compute_stream, void *copy_stream) {
@@ -431,10 +450,8 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
             }
             int32_t *row_of = io->row_of + (size_t)i * nk;
             int32_t *offs = io->expert_offsets + (size_t)i * (c.n_experts + 1);
-            rc = pgmoe_permute(ctx, x_at(i), idx_at(i), T, io->x_perm, row_of, offs, compute_stream);
-            if (rc) return rc;
             int n_partial = 0;
-            rc = expert_ffn_impl(ctx, i, io->x_perm, offs, (int)nk, io->y_perm, io->workspace, compute_stream, &n_partial);
+            rc = group_and_run_experts(ctx, io, i, T, x_at(i), idx_at(i), row_of, offs, compute_stream, &n_partial);
             if (rc) return rc;
             void *y = io->y_blocks ? (char *)io->y_blocks + (size_t)i * xbytes : nullptr;
             if (n_partial > 0)
@@ -477,12 +494,10 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
         }
         int32_t *row_of = io->row_of + (size_t)i * nk;
         int32_t *offs = io->expert_offsets + (size_t)i * (c.n_experts + 1);
-        rc = pgmoe_permute(ctx, x_at(i), idx_at(i), T, io->x_perm, row_of, offs, compute_stream);
-        if (rc) return rc;
-        // FFN, then the weighted combine; when the FFN left float32 partial sums, the combine
-        // kernel adds them itself (same order as the stand-alone reduction) and y_perm is skipped
+        // grouping + FFN, then the weighted combine; when the FFN left float32 partial sums, the
+        // combine kernel adds them itself (same order as the stand-alone reduction) and y_perm is skipped
         int n_partial = 0;
-        rc = expert_ffn_impl(ctx, i, io->x_perm, offs, (int)nk, io->y_perm, io->workspace, compute_stream, &n_partial);
+        rc = group_and_run_experts(ctx, io, i, T, x_at(i), idx_at(i), row_of, offs, compute_stream, &n_partial);
         if (rc) return rc;
         void *y = io->y_blocks ? (char *)io->y_blocks + (size_t)i * xbytes : nullptr;
         if (n_partial > 0)

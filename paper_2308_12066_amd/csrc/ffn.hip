@@ -117,7 +117,8 @@ template <int MT, int KT, int NW, int D>
 __global__ __launch_bounds__(NW * 64) void ffn_fused_kernel(
     const __bf16 *__restrict__ x_perm, const int32_t *__restrict__ offsets, int E, int f, int f_range,
     const char *__restrict__ w_base, size_t w_stride, int slot_by_rank, int n_slots,
-    const unsigned long long *__restrict__ table, float *__restrict__ partial, __bf16 *__restrict__ y_perm, int n_rows) {
+    const unsigned long long *__restrict__ table, float *__restrict__ partial, __bf16 *__restrict__ y_perm, int n_rows,
+    const int32_t *__restrict__ src_row) {  // nullable: grouped row r is row src_row[r] of x_perm (rows not gathered yet)
     constexpr int SUB = 16 * NW;      // d_ff columns per sub-slab
     constexpr int KTB = SUB / 32;     // k-tiles of phase B per sub-slab
     constexpr int NTD = KT * 2;       // n-tiles of the output (d_model / 16)
@@ -164,12 +165,15 @@ __global__ __launch_bounds__(NW * 64) void ffn_fused_kernel(
     // stage the chunk's rows (zero-filling rows beyond nrows) while the first weight tiles fly
     {
         constexpr int cells_per_row = d >> 3;
-        const uint4 *src = reinterpret_cast<const uint4 *>(x_perm + (size_t)ci.row0 * d);
+        const uint4 *src = reinterpret_cast<const uint4 *>(x_perm);
         uint4 *dst = reinterpret_cast<uint4 *>(xs);
         for (int i = tid; i < 16 * MT * cells_per_row; i += NW * 64) {
             const int m = i / cells_per_row, k8 = i - m * cells_per_row;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (m < ci.nrows) v = src[(size_t)m * cells_per_row + k8];
+            if (m < ci.nrows) {
+                const int row = ci.row0 + m;
+                v = src[(size_t)(src_row ? src_row[row] : row) * cells_per_row + k8];
+            }
             dst[(((m >> 4) * KT + (k8 >> 2)) << 6) + (m & 15) + 16 * (k8 & 3)] = v;
         }
     }
@@ -267,7 +271,8 @@ template <int KT>
 __global__ __launch_bounds__(256) void ffn_decode_kernel(
     const __bf16 *__restrict__ x_perm, const int32_t *__restrict__ offsets, int E, int f,
     const char *__restrict__ w_base, size_t w_stride, int slot_by_rank, int n_slots,
-    const unsigned long long *__restrict__ table, float *__restrict__ partial, int n_rows) {
+    const unsigned long long *__restrict__ table, float *__restrict__ partial, int n_rows,
+    const int32_t *__restrict__ src_row) {  // nullable: grouped row r is row src_row[r] of x_perm
     constexpr int d = KT * 32;
     constexpr int NTD = KT * 2;   // output n-tiles
     constexpr int NA = KT / 2;    // phase-A tiles per wavefront
@@ -304,12 +309,15 @@ __global__ __launch_bounds__(256) void ffn_decode_kernel(
     floatx4 *hsum = reinterpret_cast<floatx4 *>(xs + (size_t)KT * 64);   // [2 k-halves][2 n-tiles][64]
     {
         constexpr int cells_per_row = d >> 3;
-        const uint4 *src = reinterpret_cast<const uint4 *>(x_perm + (size_t)ci.row0 * d);
+        const uint4 *src = reinterpret_cast<const uint4 *>(x_perm);
         uint4 *dst = reinterpret_cast<uint4 *>(xs);
         for (int i = tid; i < 16 * cells_per_row; i += 256) {
             const int m = i / cells_per_row, k8 = i - m * cells_per_row;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (m < ci.nrows) v = src[(size_t)m * cells_per_row + k8];
+            if (m < ci.nrows) {
+                const int row = ci.row0 + m;
+                v = src[(size_t)(src_row ? src_row[row] : row) * cells_per_row + k8];
+            }
             dst[((k8 >> 2) << 6) + m + 16 * (k8 & 3)] = v;
         }
     }
@@ -375,7 +383,8 @@ template <bool DOWN, int WMT>
 __global__ __launch_bounds__(256) void ffn_gemm_kernel(
     const __bf16 *__restrict__ a_rows, int lda, const int32_t *__restrict__ offsets, int E, int d, int f, int n_split,
     const char *__restrict__ w_base, size_t w_stride, int slot_by_rank, int n_slots,
-    const unsigned long long *__restrict__ table, __bf16 *__restrict__ h_out, float *__restrict__ partial, int n_rows) {
+    const unsigned long long *__restrict__ table, __bf16 *__restrict__ h_out, float *__restrict__ partial, int n_rows,
+    const int32_t *__restrict__ src_row) {  // nullable: grouped row r is row src_row[r] of a_rows
     constexpr int ROWS = 32 * WMT, RT = 2 * WMT, NA = ROWS / 32;  // rows, row tiles, A loads per wavefront and stage
     __shared__ __attribute__((aligned(16))) bf16x8 a_lds[2 * RT * 64];  // [k-tile][row-tile][cell]
     __shared__ __attribute__((aligned(16))) bf16x8 w_lds[2 * 8 * 64];   // [k-tile][n-tile][cell]
@@ -426,16 +435,19 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
     // writes and the operand-order reads (lane = token + 16 * k-group) free of bank conflicts.
     auto cell_of = [](int t, int kg, int kt) { return 16 * (t >> 2) + 4 * ((t & 3) ^ ((kt & 1) << 1)) + (kg ^ (t >> 2)); };
     const int ld_row = lane >> 3, ld_kt = (lane >> 2) & 1, ld_kg = lane & 3;
-    auto request = [&](int k0, bf16x8 (&ra)[NA], bf16x8 (&rw)[4]) {
+    // where this lane's NA rows start in a_rows (rows past the chunk's end read the chunk's last
+    // row, a valid address; what is computed for them is never stored)
+    size_t a_off[NA];
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            const int r = (wave * NA + i) * 8 + ld_row;
-            // rows past the chunk's end read the chunk's last row (a valid address); what is
-            // computed for them is never stored.  Nothing may touch the loaded value before it
-            // goes to LDS, or the wait for it would move up to here and undo the prefetch.
-            const int rc = min(r, ci.nrows - 1);
-            ra[i] = *(const global_bf16x8 *)(a_rows + (size_t)(ci.row0 + rc) * lda + k0 + 8 * (lane & 7));
-        }
+    for (int i = 0; i < NA; ++i) {
+        const int row = ci.row0 + min((wave * NA + i) * 8 + ld_row, ci.nrows - 1);
+        a_off[i] = (size_t)(src_row ? src_row[row] : row) * lda + 8 * (lane & 7);
+    }
+    auto request = [&](int k0, bf16x8 (&ra)[NA], bf16x8 (&rw)[4]) {
+        // nothing may touch a loaded value before it goes to LDS, or the wait for it would move
+        // up to here and undo the prefetch
+#pragma unroll
+        for (int i = 0; i < NA; ++i) ra[i] = *(const global_bf16x8 *)(a_rows + a_off[i] + k0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int idx = wave * 4 + i, kt = idx >> 3, nt = idx & 7;
@@ -712,7 +724,7 @@ static int timing_slot(pgmoe_ctx *ctx) {
 template <int MT, int KT, int NW, int D>
 static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots,
                         const void *x_perm, const int32_t *offsets, int n_rows, void *y_perm, void *workspace,
-                        hipStream_t s, int *keep_partials, const unsigned long long *table) {
+                        hipStream_t s, int *keep_partials, const unsigned long long *table, const int32_t *src_row) {
     const pgmoe_config &c = ctx->cfg;
     const size_t lds = (size_t)MT * KT * 1024 + 2u * MT * (16 * NW / 32) * 1024;
     auto kern = ffn_fused_kernel<MT, KT, NW, D>;
@@ -728,7 +740,7 @@ static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, si
     if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_begin[tslot], s));
     hipLaunchKernelGGL(kern, dim3(p.max_chunks, p.n_partial), dim3(NW * 64), lds, s, (const __bf16 *)x_perm, offsets,
                        c.n_experts, c.d_ff, p.f_range, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, partial, (__bf16 *)y_perm,
-                       n_rows);
+                       n_rows, src_row);
     PG_HIP(ctx, hipGetLastError());
     if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
     if (keep_partials) {
@@ -754,7 +766,7 @@ static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, si
 
 int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots, const void *x_perm,
                const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s, int *keep_partials,
-               const unsigned long long *table) {
+               const unsigned long long *table, const int32_t *src_row) {
     const pgmoe_config &c = ctx->cfg;
     if (keep_partials) *keep_partials = 0;
     if (n_rows == 0) return PGMOE_OK;
@@ -786,14 +798,14 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
         const int tslot = timing_slot(ctx);
         if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_begin[tslot], s));
         const dim3 grid_up(max_chunks, c.d_ff / GEMM_COLS), grid_down(max_chunks, (c.d_model / GEMM_COLS) * GEMM_SPLIT);
-#define PG_GEMM(DOWN_, WMT_, GRID_, A_, LDA_, SPLIT_, H_, P_)                                                                  \
+#define PG_GEMM(DOWN_, WMT_, GRID_, A_, LDA_, SPLIT_, H_, P_, SRC_)                                                                  \
     hipLaunchKernelGGL((ffn_gemm_kernel<DOWN_, WMT_>), GRID_, dim3(256), 0, s, A_, LDA_, offsets, c.n_experts, c.d_model, c.d_ff, \
-                       SPLIT_, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, H_, P_, n_rows)
-        if (wmt == 8) PG_GEMM(false, 8, grid_up, (const __bf16 *)x_perm, c.d_model, 1, h, (float *)nullptr);
-        else PG_GEMM(false, 4, grid_up, (const __bf16 *)x_perm, c.d_model, 1, h, (float *)nullptr);
+                       SPLIT_, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, H_, P_, n_rows, SRC_)
+        if (wmt == 8) PG_GEMM(false, 8, grid_up, (const __bf16 *)x_perm, c.d_model, 1, h, (float *)nullptr, src_row);
+        else PG_GEMM(false, 4, grid_up, (const __bf16 *)x_perm, c.d_model, 1, h, (float *)nullptr, src_row);
         PG_HIP(ctx, hipGetLastError());
-        if (wmt == 8) PG_GEMM(true, 8, grid_down, (const __bf16 *)h, c.d_ff, GEMM_SPLIT, (__bf16 *)nullptr, partial);
-        else PG_GEMM(true, 4, grid_down, (const __bf16 *)h, c.d_ff, GEMM_SPLIT, (__bf16 *)nullptr, partial);
+        if (wmt == 8) PG_GEMM(true, 8, grid_down, (const __bf16 *)h, c.d_ff, GEMM_SPLIT, (__bf16 *)nullptr, partial, (const int32_t *)nullptr);
+        else PG_GEMM(true, 4, grid_down, (const __bf16 *)h, c.d_ff, GEMM_SPLIT, (__bf16 *)nullptr, partial, (const int32_t *)nullptr);
         PG_HIP(ctx, hipGetLastError());
 #undef PG_GEMM
         if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
@@ -821,10 +833,10 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
         const size_t lds = (size_t)kt * 1024 + 4096;
         if (kt == 24)
             hipLaunchKernelGGL(ffn_decode_kernel<24>, grid, dim3(256), lds, s, (const __bf16 *)x_perm, offsets, c.n_experts, c.d_ff,
-                               w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, partial, n_rows);
+                               w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, partial, n_rows, src_row);
         else
             hipLaunchKernelGGL(ffn_decode_kernel<32>, grid, dim3(256), lds, s, (const __bf16 *)x_perm, offsets, c.n_experts, c.d_ff,
-                               w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, partial, n_rows);
+                               w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, partial, n_rows, src_row);
         PG_HIP(ctx, hipGetLastError());
         if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
         if (keep_partials) {
@@ -839,7 +851,7 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
     }
     if (c.d_ff % (16 * p.nw)) return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: d_ff=%d is not a multiple of the %d-column sub-slab", c.d_ff, 16 * p.nw);
 #define PG_CASE(MT_, KT_, NW_, D_) \
-    if (p.mt == MT_ && kt == KT_ && p.nw == NW_) return launch_fused<MT_, KT_, NW_, D_>(ctx, p, w_base, w_stride, slot_by_rank, n_slots, x_perm, offsets, n_rows, y_perm, workspace, s, keep_partials, table)
+    if (p.mt == MT_ && kt == KT_ && p.nw == NW_) return launch_fused<MT_, KT_, NW_, D_>(ctx, p, w_base, w_stride, slot_by_rank, n_slots, x_perm, offsets, n_rows, y_perm, workspace, s, keep_partials, table, src_row)
     PG_CASE(1, 2, 4, 4); PG_CASE(1, 4, 4, 8); PG_CASE(1, 8, 4, 16); PG_CASE(1, 16, 4, 16); PG_CASE(1, 24, 4, 16);
     PG_CASE(1, 32, 4, 16); PG_CASE(1, 64, 4, 16); PG_CASE(1, 24, 2, 24); PG_CASE(1, 32, 2, 24);
     PG_CASE(2, 2, 4, 4); PG_CASE(2, 4, 4, 8); PG_CASE(2, 8, 4, 16); PG_CASE(2, 16, 4, 16); PG_CASE(2, 24, 4, 16);

@@ -1,6 +1,8 @@
 // Group tokens by expert (Sec. II-B: each activated expert processes the tokens routed to it):
 // histogram of the selected expert ids, exclusive prefix sum, stable rank of every entry
-// inside its expert's group, and the row gather x_perm[row_of[n]] = x[n / k].
+// inside its expert's group, and the row gather x_perm[row_of[n]] = x[n / k].  The whole-stack
+// step skips the gather: route_kernel also writes the inverse map (grouped row -> token) and the
+// expert kernels read their rows through it.
 //
 // route_kernel: one workgroup of 1024 threads (16 wavefronts).  Pass 1 counts with LDS
 // atomics (integer, so order does not matter).  Pass 2 walks the entries in order, 1024 at
@@ -15,9 +17,10 @@ namespace pgmoe {
 constexpr int ROUTE_THREADS = 1024;
 constexpr int ROUTE_WAVES = ROUTE_THREADS / 64;
 
-__global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(const int32_t *__restrict__ idx, int n, int E,
+__global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(const int32_t *__restrict__ idx, int n, int E, int k,
                                                                int32_t *__restrict__ row_of,
-                                                               int32_t *__restrict__ offsets, uint32_t *flags) {
+                                                               int32_t *__restrict__ offsets,
+                                                               int32_t *__restrict__ src_row, uint32_t *flags) {
     __shared__ int cnt[PGMOE_MAX_EXPERTS];
     __shared__ int scan[PGMOE_MAX_EXPERTS];
     __shared__ int base[PGMOE_MAX_EXPERTS];
@@ -90,7 +93,11 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(const int32_t *__r
             base[tid] = run;
         }
         __syncthreads();
-        if (valid) row_of[i] = wbase[wave][e] + rank_in_wave;
+        if (valid) {
+            const int r = wbase[wave][e] + rank_in_wave;
+            row_of[i] = r;
+            if (src_row) src_row[r] = i / k;  // the inverse map: which token's row sits in grouped row r
+        }
         if (leader) whist[wave][e] = 0;
         __syncthreads();
     }
@@ -109,13 +116,21 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const char *__restrict
     for (int i = lane; i < nv; i += 64) dst[i] = src[i];
 }
 
+int launch_route(pgmoe_ctx *ctx, const int32_t *idx, int T, int32_t *row_of, int32_t *offsets, int32_t *src_row,
+                 hipStream_t s) {
+    const pgmoe_config &c = ctx->cfg;
+    hipLaunchKernelGGL(route_kernel, dim3(1), dim3(ROUTE_THREADS), 0, s, idx, T * c.top_k, c.n_experts, c.top_k, row_of,
+                       offsets, src_row, ctx->dev_flags);
+    PG_HIP(ctx, hipGetLastError());
+    return PGMOE_OK;
+}
+
 int launch_permute(pgmoe_ctx *ctx, const void *x, const int32_t *idx, int T, void *x_perm, int32_t *row_of,
                    int32_t *offsets, hipStream_t s) {
     const pgmoe_config &c = ctx->cfg;
     const int n = T * c.top_k;
-    hipLaunchKernelGGL(route_kernel, dim3(1), dim3(ROUTE_THREADS), 0, s, idx, n, c.n_experts, row_of, offsets,
-                       ctx->dev_flags);
-    PG_HIP(ctx, hipGetLastError());
+    const int rc = launch_route(ctx, idx, T, row_of, offsets, nullptr, s);
+    if (rc) return rc;
     if (n == 0) return PGMOE_OK;
     const int row_bytes = c.d_model * (int)ctx->elem;
     const int grid = (n + 3) / 4;

@@ -52,6 +52,7 @@ struct pgmoe_ctx {
     char *slot_pool;       // [n_gen][slots][expert_bytes]
     uint32_t *dev_flags;   // sticky condition bits
     int32_t *dev_unique;   // [n_blocks] distinct experts found by the pull kernel (dev_flags + 64 bytes)
+    int32_t *dev_src_row;  // [max_tokens * k] grouped row -> token, written by the routing of the block in flight
     const char *store_dev; // device-visible address of the pinned host store
     bool pull;             // fetch with the device-side pull kernel
     int32_t *idx_staging;  // pinned host [max_tokens * k]
@@ -124,11 +125,15 @@ int launch_gate(pgmoe_ctx *ctx, const void *x, const void *w, const float *bias,
                 float *prob, float *probs, hipStream_t s);
 int launch_permute(pgmoe_ctx *ctx, const void *x, const int32_t *idx, int T, void *x_perm,
                    int32_t *row_of, int32_t *offsets, hipStream_t s);
+// The integer half of launch_permute; src_row (nullable) receives the inverse map grouped row -> token.
+int launch_route(pgmoe_ctx *ctx, const int32_t *idx, int T, int32_t *row_of, int32_t *offsets, int32_t *src_row,
+                 hipStream_t s);
 // keep_partials != nullptr: if the launch produces float32 partial sums, leave them in the
 // workspace unreduced and report their number there (0 = y_perm was written directly).
 int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots, const void *x_perm,
                const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s, int *keep_partials = nullptr,
-               const unsigned long long *table = nullptr);  // table: per-expert weight addresses (0 = none), overrides w_base
+               const unsigned long long *table = nullptr,  // table: per-expert weight addresses (0 = none), overrides w_base
+               const int32_t *src_row = nullptr);  // bf16 only: x_perm is the un-grouped x [T,d], grouped row r reads x[src_row[r]]
 // p-lanes of the partial-sum reduction for P partials (fixes the order of the additions)
 inline int reduce_lanes(int P) { return P <= 2 ? 1 : (P <= 8 ? 4 : 16); }
 // Combine straight from P unreduced float32 partials [P][n_rows][d] (bf16 contexts only): same
