@@ -169,7 +169,10 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
         c->ffn_recorded[g] = false;
     }
     c->stats = new (std::nothrow) BlockStats[cfg->n_blocks]();
-    if (!c->stats) {
+    c->routed = new (std::nothrow) bool[cfg->n_blocks]();
+    if (!c->stats || !c->routed) {
+        delete[] c->stats;
+        delete[] c->routed;
         delete c;
         return fail(nullptr, PGMOE_EINVAL, "pgmoe_create: out of host memory");
     }
@@ -191,7 +194,7 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
         if (rc == PGMOE_OK) H(hipMemset(c->dev_flags, 0, flag_bytes), "hipMemset(flags)");
         c->dev_unique = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(c->dev_flags) + 64);
         size_t n_idx = (size_t)cfg->max_tokens * cfg->top_k;
-        if (rc == PGMOE_OK) H(hipMalloc((void **)&c->dev_src_row, n_idx * sizeof(int32_t)), "hipMalloc(src_row)");
+        if (rc == PGMOE_OK) H(hipMalloc((void **)&c->dev_src_row, (size_t)cfg->n_blocks * n_idx * sizeof(int32_t)), "hipMalloc(src_row)");
         if (rc == PGMOE_OK) H(hipHostMalloc((void **)&c->idx_staging, n_idx * sizeof(int32_t), hipHostMallocDefault), "hipHostMalloc(idx staging)");
         if (rc == PGMOE_OK) H(hipEventCreateWithFlags(&c->idx_ready, hipEventDisableTiming), "hipEventCreate");
         if (rc == PGMOE_OK) H(hipStreamCreateWithFlags(&c->copy2, hipStreamNonBlocking), "hipStreamCreate");
@@ -246,6 +249,7 @@ int pgmoe_destroy(pgmoe_ctx *c) {
         free_timing(c);
     }
     delete[] c->stats;
+    delete[] c->routed;
     delete c;
     return PGMOE_OK;
 }

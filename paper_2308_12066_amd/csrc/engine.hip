@@ -384,6 +384,20 @@ int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_
     return expert_ffn_impl(ctx, block, x_perm, expert_offsets, n_rows, y_perm, workspace, stream, nullptr);
 }
 
+// The gate that routes block g, evaluated on hidden state x, inside pgmoe_stack_step.  For a
+// decode-sized bf16 batch the gate kernel also groups block g's tokens by expert (offsets, row_of,
+// inverse map) and routed[g] says so; pgmoe_stack_step has validated the buffers.
+static int gate_for_block(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int g, const void *x, int T, void *stream) {
+    const pgmoe_config &c = ctx->cfg;
+    const size_t nk = (size_t)T * c.top_k;
+    const float *bias = io->gate_b ? io->gate_b[g] : nullptr;
+    if (!aligned(x, 16) || !aligned(io->gate_w[g], 16) || !aligned(bias, 4))
+        return fail(ctx, PGMOE_EINVAL, "pgmoe_stack_step: misaligned hidden state, gate weight or bias of block %d", g);
+    return launch_gate(ctx, x, io->gate_w[g], bias, T, io->topk_idx + (size_t)g * nk, io->topk_prob + (size_t)g * nk, nullptr,
+                       (hipStream_t)stream, io->row_of + (size_t)g * nk, io->expert_offsets + (size_t)g * (c.n_experts + 1),
+                       ctx->dev_src_row + (size_t)g * c.max_tokens * c.top_k, &ctx->routed[g]);
+}
+
 // Token grouping and expert FFN of one block inside pgmoe_stack_step.  bf16: only the integer
 // half of the grouping runs (offsets, row_of and the inverse map grouped row -> token); the FFN
 // kernels read their rows of x through that map, so the gather kernel and the x_perm round trip
@@ -396,9 +410,12 @@ static int group_and_run_experts(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, i
         if (rc) return rc;
         return expert_ffn_impl(ctx, block, io->x_perm, offs, nk, io->y_perm, io->workspace, stream, n_partial);
     }
-    int rc = launch_route(ctx, idx, T, row_of, offs, ctx->dev_src_row, (hipStream_t)stream);
-    if (rc) return rc;
-    return expert_ffn_impl(ctx, block, x, offs, nk, io->y_perm, io->workspace, stream, n_partial, ctx->dev_src_row);
+    int32_t *src_row = ctx->dev_src_row + (size_t)block * ctx->cfg.max_tokens * ctx->cfg.top_k;
+    if (!ctx->routed[block]) {  // the gate kernel that routed this block did not group its tokens itself
+        int rc = launch_route(ctx, idx, T, row_of, offs, src_row, (hipStream_t)stream);
+        if (rc) return rc;
+    }
+    return expert_ffn_impl(ctx, block, x, offs, nk, io->y_perm, io->workspace, stream, n_partial, src_row);
 }
 
 int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *compute_stream, void *copy_stream) {
@@ -409,6 +426,10 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     if (!io->gate_w || !io->x_states || !io->topk_idx || !io->topk_prob || !io->row_of || !io->expert_offsets ||
         !io->x_perm || !io->y_perm || !io->workspace)
         return fail(ctx, PGMOE_EINVAL, "%s: a required buffer is NULL", fn);
+    if (!aligned(io->x_states, 16) || !aligned(io->x_perm, 16) || !aligned(io->y_perm, 16) || !aligned(io->workspace, 256) ||
+        !aligned(io->topk_idx, 4) || !aligned(io->topk_prob, 4) || !aligned(io->row_of, 4) || !aligned(io->expert_offsets, 4) ||
+        !aligned(io->y_blocks, 16))
+        return fail(ctx, PGMOE_EINVAL, "%s: misaligned buffer (activations 16, workspace 256, index arrays 4 bytes)", fn);
     const pgmoe_config &c = ctx->cfg;
     const int L = c.n_blocks;
     for (int g = 0; g < L; ++g)
@@ -416,13 +437,13 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     if (ctx->store_mode == STORE_NONE) return fail(ctx, PGMOE_ESTATE, "%s: no expert store registered", fn);
     if (ctx->host_only) return fail(ctx, PGMOE_ENODEVICE, "%s: context is host-only, nothing can be launched", fn);
     if (T == 0) return PGMOE_OK;
+    for (int b = 0; b < L; ++b) ctx->routed[b] = false;
 
     const size_t xbytes = (size_t)T * c.d_model * ctx->elem;
     const size_t nk = (size_t)T * c.top_k;
     auto x_at = [&](int i) { return (char *)io->x_states + (size_t)i * xbytes; };
     auto idx_at = [&](int i) { return io->topk_idx + (size_t)i * nk; };
     auto prob_at = [&](int i) { return io->topk_prob + (size_t)i * nk; };
-    auto bias_at = [&](int g) -> const float * { return io->gate_b ? io->gate_b[g] : nullptr; };
     int rc;
 
     if (ctx->schedule != PGMOE_SCHED_PREGATED) {
@@ -438,7 +459,7 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
         }
         for (int i = 0; i < L; ++i) {
             if (ctx->trace) PG_HIP(ctx, hipEventRecord(ctx->ev_c0[i], (hipStream_t)compute_stream));
-            rc = pgmoe_pregate_topk(ctx, x_at(i), io->gate_w[i], bias_at(i), T, idx_at(i), prob_at(i), nullptr, compute_stream);
+            rc = gate_for_block(ctx, io, i, x_at(i), T, compute_stream);
             if (rc) return rc;
             if (host && !prefetch) {
                 rc = pgmoe_fetch_experts(ctx, i, idx_at(i), T, compute_stream, ctx->pull ? compute_stream : copy_stream, nullptr);
@@ -476,7 +497,7 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     const int N = ctx->distance;
     const int head = std::min(N, L - 1);
     for (int g = 0; g <= head; ++g) {
-        rc = pgmoe_pregate_topk(ctx, x_at(0), io->gate_w[g], bias_at(g), T, idx_at(g), prob_at(g), nullptr, compute_stream);
+        rc = gate_for_block(ctx, io, g, x_at(0), T, compute_stream);
         if (rc) return rc;
         rc = pgmoe_fetch_experts(ctx, g, idx_at(g), T, compute_stream, copy_stream, nullptr);
         if (rc) return rc;
@@ -487,7 +508,7 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
         // the pre-gate of block i routes block i+N; its experts start moving before block i executes
         if (i > 0 && i + N < L) {
             const int g = i + N;
-            rc = pgmoe_pregate_topk(ctx, x_at(i), io->gate_w[g], bias_at(g), T, idx_at(g), prob_at(g), nullptr, compute_stream);
+            rc = gate_for_block(ctx, io, g, x_at(i), T, compute_stream);
             if (rc) return rc;
             rc = pgmoe_fetch_experts(ctx, g, idx_at(g), T, compute_stream, copy_stream, nullptr);
             if (rc) return rc;

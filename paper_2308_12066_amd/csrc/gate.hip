@@ -43,7 +43,8 @@ __device__ inline void group_argmax(float &v, int &i) {
 // experts s, s+16, s+32, ... (at most 16 of them, E <= 256).
 __device__ inline void softmax_topk(const float *zs, int zstride, int t0, int nt, int E, int k,
                                     int32_t *__restrict__ idx_out, float *__restrict__ prob_out,
-                                    float *__restrict__ probs_out, uint32_t *flags) {
+                                    float *__restrict__ probs_out, uint32_t *flags,
+                                    int32_t *idx_lds = nullptr) {  // nullable: LDS copy [nt*k] of the chosen indices
     const int tid = threadIdx.x;
     const int sub = tid & 15, grp = tid >> 4;  // 16 groups per 256-thread workgroup
     bool any_nan = false;
@@ -100,6 +101,7 @@ __device__ inline void softmax_topk(const float *zs, int zstride, int t0, int nt
             if (sub == 0 && live) {
                 idx_out[tok * k + j] = bi;
                 prob_out[tok * k + j] = expf(bv - m) * inv;
+                if (idx_lds) idx_lds[t * k + j] = bi;
             }
         }
     }
@@ -243,11 +245,13 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_vec_kernel(
 typedef __bf16 gbf16x8 __attribute__((ext_vector_type(8)));
 typedef float gfloatx4 __attribute__((ext_vector_type(4)));
 constexpr int GM_TOK = 16;  // tokens per workgroup
+constexpr int GATE_ROUTE_MAX = 256;  // most (token, choice) pairs the gate kernel groups by itself
 
 template <int NP>  // passes of 128 experts (1: E <= 128, 2: E <= 256)
 __global__ __launch_bounds__(GATE_THREADS) void gate_topk_mfma_kernel(
     const __bf16 *__restrict__ x, const __bf16 *__restrict__ w, const float *__restrict__ bias, int T, int d, int E, int k,
-    int32_t *__restrict__ idx_out, float *__restrict__ prob_out, float *__restrict__ probs_out, uint32_t *flags) {
+    int32_t *__restrict__ idx_out, float *__restrict__ prob_out, float *__restrict__ probs_out, uint32_t *flags,
+    int32_t *__restrict__ row_of, int32_t *__restrict__ offsets, int32_t *__restrict__ src_row) {  // routing outputs: see below
     extern __shared__ __attribute__((aligned(16))) char gsm[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g = lane >> 4;
@@ -329,7 +333,39 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_mfma_kernel(
         zs[o] = sum + ((bias && e < E) ? bias[e] : 0.f);
     }
     __syncthreads();
-    softmax_topk(zs, ecols, t0, nt, E, k, idx_out, prob_out, probs_out, flags);
+    // Decode-sized batch (the whole batch in this one workgroup, at most GATE_ROUTE_MAX
+    // selections): group the tokens by expert right here instead of in a kernel of its own.
+    // Same integers as route_kernel: counts, exclusive prefix sum, stable rank, inverse map.
+    const bool route = row_of != nullptr;   // uniform; the host passes it only for a single-workgroup launch
+    int32_t *r_idx = reinterpret_cast<int32_t *>(part);      // [n]   (the partial planes are dead by now)
+    int32_t *r_cnt = r_idx + GATE_ROUTE_MAX;                 // [E]
+    int32_t *r_off = r_cnt + PGMOE_MAX_EXPERTS;              // [E]
+    softmax_topk(zs, ecols, t0, nt, E, k, idx_out, prob_out, probs_out, flags, route ? r_idx : nullptr);
+    if (!route) return;
+    const int n_sel = nt * k;
+    __syncthreads();
+    for (int e = tid; e < E; e += GATE_THREADS) {
+        int c = 0;
+        for (int i = 0; i < n_sel; ++i) c += r_idx[i] == e ? 1 : 0;
+        r_cnt[e] = c;
+    }
+    __syncthreads();
+    for (int e = tid; e < E; e += GATE_THREADS) {
+        int o = 0;
+        for (int q = 0; q < e; ++q) o += r_cnt[q];
+        r_off[e] = o;
+        offsets[e] = o;
+    }
+    if (tid == 0) offsets[E] = n_sel;
+    __syncthreads();
+    for (int i = tid; i < n_sel; i += GATE_THREADS) {
+        const int e = r_idx[i];
+        int rank = 0;
+        for (int q = 0; q < i; ++q) rank += r_idx[q] == e ? 1 : 0;
+        const int r = r_off[e] + rank;
+        row_of[i] = r;
+        src_row[r] = i / k;
+    }
 }
 
 template <typename XT>
@@ -354,14 +390,19 @@ static void launch_gate_t(const pgmoe_config &c, const XT *x, const XT *w, const
 }
 
 static int launch_gate_mfma(pgmoe_ctx *ctx, const __bf16 *x, const __bf16 *w, const float *bias, int T, int32_t *idx,
-                            float *prob, float *probs, hipStream_t s) {
+                            float *prob, float *probs, hipStream_t s, int32_t *row_of, int32_t *offsets, int32_t *src_row,
+                            bool *routed) {
     const pgmoe_config &c = ctx->cfg;
     const int np = c.n_experts <= 128 ? 1 : 2;
     const size_t lds = (size_t)5 * GM_TOK * np * 128 * sizeof(float);  // 4 partial planes + the logits
     const dim3 grid((T + GM_TOK - 1) / GM_TOK);
+    // grouping inside the gate kernel: one workgroup holds the whole batch and the selections fit
+    const bool route = row_of && offsets && src_row && grid.x == 1 && T * c.top_k <= GATE_ROUTE_MAX;
+    if (!route) row_of = offsets = src_row = nullptr;
+    if (routed) *routed = route;
     if (np == 1) {
         hipLaunchKernelGGL(gate_topk_mfma_kernel<1>, grid, dim3(GATE_THREADS), lds, s, x, w, bias, T, c.d_model, c.n_experts,
-                           c.top_k, idx, prob, probs, ctx->dev_flags);
+                           c.top_k, idx, prob, probs, ctx->dev_flags, row_of, offsets, src_row);
     } else {
         auto kern = gate_topk_mfma_kernel<2>;
         static thread_local bool attr_set = false;
@@ -370,17 +411,19 @@ static int launch_gate_mfma(pgmoe_ctx *ctx, const __bf16 *x, const __bf16 *w, co
             attr_set = true;
         }
         hipLaunchKernelGGL(kern, grid, dim3(GATE_THREADS), lds, s, x, w, bias, T, c.d_model, c.n_experts, c.top_k, idx, prob,
-                           probs, ctx->dev_flags);
+                           probs, ctx->dev_flags, row_of, offsets, src_row);
     }
     PG_HIP(ctx, hipGetLastError());
     return PGMOE_OK;
 }
 
 int launch_gate(pgmoe_ctx *ctx, const void *x, const void *w, const float *bias, int T, int32_t *idx,
-                float *prob, float *probs, hipStream_t s) {
+                float *prob, float *probs, hipStream_t s, int32_t *row_of, int32_t *offsets, int32_t *src_row, bool *routed) {
     const pgmoe_config &c = ctx->cfg;
+    if (routed) *routed = false;
     if (c.dtype == PGMOE_BF16 && c.n_experts % 8 == 0 && c.d_model % 32 == 0 && !getenv("PGMOE_GATE_NO_MFMA"))
-        return launch_gate_mfma(ctx, (const __bf16 *)x, (const __bf16 *)w, bias, T, idx, prob, probs, s);
+        return launch_gate_mfma(ctx, (const __bf16 *)x, (const __bf16 *)w, bias, T, idx, prob, probs, s,
+                                getenv("PGMOE_GATE_NO_ROUTE") ? nullptr : row_of, offsets, src_row, routed);
     if (c.dtype == PGMOE_F32)
         launch_gate_t<float>(c, (const float *)x, (const float *)w, bias, T, idx, prob, probs, ctx->dev_flags, s);
     else

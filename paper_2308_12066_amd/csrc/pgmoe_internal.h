@@ -52,7 +52,8 @@ struct pgmoe_ctx {
     char *slot_pool;       // [n_gen][slots][expert_bytes]
     uint32_t *dev_flags;   // sticky condition bits
     int32_t *dev_unique;   // [n_blocks] distinct experts found by the pull kernel (dev_flags + 64 bytes)
-    int32_t *dev_src_row;  // [max_tokens * k] grouped row -> token, written by the routing of the block in flight
+    int32_t *dev_src_row;  // [n_blocks][max_tokens * k] grouped row -> token, written by each block's routing
+    bool *routed;          // [n_blocks] host: this step's gate kernel already grouped the block's tokens
     const char *store_dev; // device-visible address of the pinned host store
     bool pull;             // fetch with the device-side pull kernel
     int32_t *idx_staging;  // pinned host [max_tokens * k]
@@ -121,8 +122,12 @@ size_t ffn_workspace_bytes(const pgmoe_config &cfg);
 const char *ffn_kernel_name(const pgmoe_config &cfg, int n_rows);
 
 // Kernel launchers (each validates nothing: callers did).  All asynchronous on `s`.
+// row_of / offsets / src_row / routed (all or none): if the launch can also group the tokens by
+// expert (decode-sized batch, bf16 matrix-core gate), it writes what launch_route would and sets
+// *routed; otherwise *routed = false and the three arrays are left alone.
 int launch_gate(pgmoe_ctx *ctx, const void *x, const void *w, const float *bias, int T, int32_t *idx,
-                float *prob, float *probs, hipStream_t s);
+                float *prob, float *probs, hipStream_t s, int32_t *row_of = nullptr, int32_t *offsets = nullptr,
+                int32_t *src_row = nullptr, bool *routed = nullptr);
 int launch_permute(pgmoe_ctx *ctx, const void *x, const int32_t *idx, int T, void *x_perm,
                    int32_t *row_of, int32_t *offsets, hipStream_t s);
 // The integer half of launch_permute; src_row (nullable) receives the inverse map grouped row -> token.
