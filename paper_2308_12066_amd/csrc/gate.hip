@@ -314,23 +314,26 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_mfma_kernel(
                     acc[p][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, cells[p][q], acc[p][q], 0, 0, 0);
         }
     }
-    // lane holds tokens 4*g + r (r = 0..3), column n of product q = expert 8*(n + 16*p) + q
+    // lane holds tokens 4*g + r (r = 0..3), column n of product q = expert 8*(n + 16*p) + q.  The
+    // partial logits are parked as [wave][p][q][r][lane] planes (lane-contiguous: no bank conflicts)
+    // and added over the four wavefronts in wave order.
 #pragma unroll
     for (int p = 0; p < NP; ++p)
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            const int e = 8 * (n + 16 * p) + q;
-            float *dst = part + ((size_t)wave * GM_TOK + 4 * g) * ecols + e;
-            dst[0 * ecols] = acc[p][q].x;
-            dst[1 * ecols] = acc[p][q].y;
-            dst[2 * ecols] = acc[p][q].z;
-            dst[3 * ecols] = acc[p][q].w;
+            float *dst = part + ((((size_t)wave * NP + p) * 8 + q) * 4) * 64 + lane;
+            dst[0 * 64] = acc[p][q].x;
+            dst[1 * 64] = acc[p][q].y;
+            dst[2 * 64] = acc[p][q].z;
+            dst[3 * 64] = acc[p][q].w;
         }
     __syncthreads();
-    for (int o = tid; o < GM_TOK * ecols; o += GATE_THREADS) {
-        const int e = o % ecols;
-        const float sum = ((part[o] + part[GM_TOK * ecols + o]) + part[2 * GM_TOK * ecols + o]) + part[3 * GM_TOK * ecols + o];
-        zs[o] = sum + ((bias && e < E) ? bias[e] : 0.f);
+    constexpr int PLANE = NP * 8 * 4 * 64;  // floats per wavefront
+    for (int o = tid; o < PLANE; o += GATE_THREADS) {
+        const int l = o & 63, r = (o >> 6) & 3, q = (o >> 8) & 7, p = o >> 11;
+        const int e = 8 * ((l & 15) + 16 * p) + q, tokl = 4 * (l >> 4) + r;
+        const float sum = ((part[o] + part[PLANE + o]) + part[2 * PLANE + o]) + part[3 * PLANE + o];
+        zs[tokl * ecols + e] = sum + ((bias && e < E) ? bias[e] : 0.f);
     }
     __syncthreads();
     // Decode-sized batch (the whole batch in this one workgroup, at most GATE_ROUTE_MAX
