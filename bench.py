@@ -91,7 +91,7 @@ def measured_peaks():
 
 def pmc_traffic(workload_name):
     """HBM bytes per FFN launch from the committed rocprofv3 --pmc summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", "ffn_fused_hbm_traffic.md")
+    path = os.path.join(ROOT, "profiles", "expert_ffn_hbm_traffic.md")
     try:
         m = re.search(r"^traffic_bytes_per_launch\[%s\]\s*=\s*([0-9.eE+]+)" % re.escape(workload_name),
                       open(path).read(), flags=re.M)
