@@ -550,6 +550,9 @@ def test_pull_fetch_with_too_few_slots_flags_and_zeroes(hx):
 @pytest.mark.parametrize("dtype,T,d,f,E,k,L,offloaded", [
     ("bf16", 40, 128, 256, 16, 2, 4, True), ("bf16", 1, 768, 3072, 8, 1, 3, True), ("bf16", 300, 256, 512, 8, 1, 3, False),
     ("f32", 32, 64, 256, 8, 1, 2, False),
+    # decode-sized batches, where the gate kernel groups the tokens itself: at its limit of 256
+    # selections, just beyond it (separate grouping kernel again), and with 256 experts
+    ("bf16", 16, 128, 256, 32, 16, 3, False), ("bf16", 16, 128, 256, 32, 17, 3, False), ("bf16", 7, 128, 256, 256, 3, 3, True),
 ])
 def test_stack_step_equals_the_primitive_call_sequence(hx, dtype, T, d, f, E, k, L, offloaded):
     """pgmoe_stack_step (which fuses the partial-sum reduction into the combine and orders the
@@ -582,6 +585,7 @@ def test_stack_step_equals_the_primitive_call_sequence(hx, dtype, T, d, f, E, k,
         ctx.combine(y_perm, row_of, prob[i], T, y, xs[i], xn, comp)
         torch.cuda.synchronize()
         assert torch.equal(idx[i], stack.topk_idx[i]) and torch.equal(prob[i], stack.topk_prob[i])
+        assert torch.equal(row_of, stack.row_of[i]) and torch.equal(offs, stack.expert_offsets[i]), f"block {i}: grouping"
         assert torch.equal(y, stack.y_blocks[i]), f"block {i}: y differs between stack_step and the primitives"
         assert torch.equal(xn, stack.x_states[i + 1])
         xs.append(xn)
