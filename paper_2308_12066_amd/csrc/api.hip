@@ -196,7 +196,7 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
         size_t n_idx = (size_t)cfg->max_tokens * cfg->top_k;
         if (rc == PGMOE_OK) H(hipMalloc((void **)&c->dev_src_row, (size_t)cfg->n_blocks * n_idx * sizeof(int32_t)), "hipMalloc(src_row)");
         if (rc == PGMOE_OK) H(hipHostMalloc((void **)&c->idx_staging, n_idx * sizeof(int32_t), hipHostMallocDefault), "hipHostMalloc(idx staging)");
-        if (rc == PGMOE_OK) H(hipEventCreateWithFlags(&c->idx_ready, hipEventDisableTiming), "hipEventCreate");
+        if (rc == PGMOE_OK) H(hipEventCreateWithFlags(&c->idx_ready, hipEventDisableTiming | hipEventReleaseToDevice), "hipEventCreate");
         if (rc == PGMOE_OK) H(hipStreamCreateWithFlags(&c->copy2, hipStreamNonBlocking), "hipStreamCreate");
         for (int g = 0; g < kGen && rc == PGMOE_OK; ++g) {
             // these two only order device work against device work: no host-visible release needed
