@@ -67,3 +67,13 @@ def test_activated_expert_sweep_points_share_weights_and_differ_only_in_top_k():
     assert (a.d_model, a.d_ff, a.n_experts, a.tokens, a.index) == (768, 3072, 64, 1, b.index) and b.top_k == b.n_experts
     assert np.array_equal(W.pregate_weight(a, 0), W.pregate_weight(b, 0))
     assert np.array_equal(W.step_input(a, 3), W.step_input(b, 3))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build is one GPU's share of the path: bench.py says so instead of launching ranks."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
