@@ -265,6 +265,14 @@ int pgmoe_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, con
 #define PGMOE_SCHED_PREFETCH_ALL 2
 int pgmoe_set_schedule(pgmoe_ctx *ctx, int schedule);
 
+/* Sensitivity aid, off by default (0): after every block's combine, pgmoe_stack_step keeps the
+ * compute stream busy for `microseconds` with a kernel that does nothing but watch the clock: a
+ * stand-in for the non-MoE layers (attention, the dense FFN layers) that sit between two MoE
+ * blocks in the real model and that the paper's migration also hides behind (Sec. IV-C).  It
+ * changes no result.  The kernel leaves after the given time or after a fixed number of clock
+ * reads, whichever comes first.  0 <= microseconds <= 100000. */
+int pgmoe_set_nonmoe_standin(pgmoe_ctx *ctx, float microseconds);
+
 typedef struct {
     const void *const *gate_w;  /* host [L] -> dev [d,E] */
     const float *const *gate_b; /* host [L] -> dev [E] | NULL; may itself be NULL */

@@ -29,7 +29,7 @@ EXPORTS = [
     "pgmoe_register_resident_experts", "pgmoe_fetch_experts", "pgmoe_get_fetch_stats", "pgmoe_unique_experts",
     "pgmoe_permute", "pgmoe_expert_ffn", "pgmoe_combine", "pgmoe_stack_step", "pgmoe_device_flags",
     "pgmoe_ffn_timing_begin", "pgmoe_ffn_timing_end", "pgmoe_slot_address", "pgmoe_fetch_timing", "pgmoe_trace", "pgmoe_get_block_trace", "pgmoe_fetch_all_experts", "pgmoe_set_schedule",
-    "pgmoe_ffn_kernel_name",
+    "pgmoe_ffn_kernel_name", "pgmoe_set_nonmoe_standin",
 ]
 
 
@@ -103,6 +103,7 @@ def _load():
     L.pgmoe_trace.argtypes = [vp, i]
     L.pgmoe_fetch_all_experts.argtypes = [vp, i, vp, vp]
     L.pgmoe_set_schedule.argtypes = [vp, i]
+    L.pgmoe_set_nonmoe_standin.argtypes = [vp, c_float]
     L.pgmoe_get_block_trace.argtypes = [vp, i, POINTER(BlockTrace)]
     L.pgmoe_slot_address.argtypes = [vp, i, i, POINTER(vp)]
     L.pgmoe_ffn_timing_end.argtypes = [vp, POINTER(c_int), POINTER(c_float), POINTER(c_float)]
@@ -290,3 +291,6 @@ class Context:
 
     def set_schedule(self, schedule: int):
         self._check(lib.pgmoe_set_schedule(self._h, schedule))
+
+    def set_nonmoe_standin(self, microseconds: float):
+        self._check(lib.pgmoe_set_nonmoe_standin(self._h, microseconds))

@@ -245,6 +245,14 @@ int pgmoe_set_schedule(pgmoe_ctx *ctx, int schedule) {
     return PGMOE_OK;
 }
 
+int pgmoe_set_nonmoe_standin(pgmoe_ctx *ctx, float microseconds) {
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "pgmoe_set_nonmoe_standin: ctx is NULL");
+    if (!(microseconds >= 0.f && microseconds <= 100000.f))
+        return fail(ctx, PGMOE_EINVAL, "pgmoe_set_nonmoe_standin: %g us outside 0..100000", (double)microseconds);
+    ctx->standin_us = microseconds;
+    return PGMOE_OK;
+}
+
 int pgmoe_get_fetch_stats(pgmoe_ctx *ctx, int block, pgmoe_fetch_stats *out) {
     const char *fn = "pgmoe_get_fetch_stats";
     if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
@@ -384,6 +392,23 @@ int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_
     return expert_ffn_impl(ctx, block, x_perm, expert_offsets, n_rows, y_perm, workspace, stream, nullptr);
 }
 
+// Stand-in for the non-MoE layers between two MoE blocks: one wavefront watches the constant
+// 100 MHz clock until `ticks` have passed; the loop is also bounded by a fixed number of clock
+// reads (each takes well over 10 ns), so the kernel ends in any case.
+__global__ void nonmoe_standin_kernel(unsigned long long ticks, unsigned long long max_reads) {
+    const unsigned long long t0 = wall_clock64();
+    for (unsigned long long i = 0; i < max_reads; ++i)
+        if (wall_clock64() - t0 >= ticks) break;
+}
+
+static int launch_standin(pgmoe_ctx *ctx, void *stream) {
+    if (ctx->standin_us <= 0.f) return PGMOE_OK;
+    const unsigned long long ticks = (unsigned long long)(ctx->standin_us * 100.f);  // 100 MHz
+    hipLaunchKernelGGL(nonmoe_standin_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, ticks, ticks * 10ull + 1000ull);
+    PG_HIP(ctx, hipGetLastError());
+    return PGMOE_OK;
+}
+
 // The gate that routes block g, evaluated on hidden state x, inside pgmoe_stack_step.  For a
 // decode-sized bf16 batch the gate kernel also groups block g's tokens by expert (offsets, row_of,
 // inverse map) and routed[g] says so; pgmoe_stack_step has validated the buffers.
@@ -481,6 +506,8 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
             else
                 rc = pgmoe_combine(ctx, io->y_perm, row_of, prob_at(i), T, y, x_at(i), x_at(i + 1), compute_stream);
             if (rc) return rc;
+            rc = launch_standin(ctx, compute_stream);
+            if (rc) return rc;
             if (ctx->trace) {
                 PG_HIP(ctx, hipEventRecord(ctx->ev_c1[i], (hipStream_t)compute_stream));
                 ctx->traced[i] = host && ctx->fetch_timing;
@@ -526,6 +553,8 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
                                          x_at(i), x_at(i + 1), (hipStream_t)compute_stream);
         else
             rc = pgmoe_combine(ctx, io->y_perm, row_of, prob_at(i), T, y, x_at(i), x_at(i + 1), compute_stream);
+        if (rc) return rc;
+        rc = launch_standin(ctx, compute_stream);
         if (rc) return rc;
         if (ctx->trace) {
             PG_HIP(ctx, hipEventRecord(ctx->ev_c1[i], (hipStream_t)compute_stream));

@@ -78,6 +78,7 @@ struct pgmoe_ctx {
     int32_t *cache_stats;             // [n_blocks][4] device: unique, copies, hits
     unsigned char *cache_parity;      // [n_blocks] host: which state copy is current
     int schedule;                           // PGMOE_SCHED_*
+    float standin_us;                       // non-MoE stand-in per block (0 = none)
     bool fetch_timing;               // record fetch_begin / fetch_end
     bool trace;                      // record the per-block compute-stream events below
     hipEvent_t *ev_c0, *ev_ready, *ev_waited, *ev_c1;  // [n_blocks] each

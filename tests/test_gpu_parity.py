@@ -466,6 +466,34 @@ def test_stack_step_replays_from_a_captured_graph(hx, offloaded):
     stack.close()
 
 
+def test_nonmoe_standin_changes_the_time_not_the_results(hx):
+    """The clock-watching stand-in for the non-MoE layers only occupies the compute stream."""
+    import time
+    H, B = hx
+    w = small_workload("bf16", 4, 128, 256, 8, 1, L=4, offloaded=True, index=57)
+    stack, gates, cache = make_stack(H, w)
+    stack.set_input(W.step_input(w, 0))
+    stack.step()
+    torch.cuda.synchronize()
+    ref = stack.x_states.clone()
+    t0 = time.perf_counter()
+    stack.step()
+    torch.cuda.synchronize()
+    plain = time.perf_counter() - t0
+    stack.ctx.set_nonmoe_standin(2000.0)
+    stack.x_states[1:].zero_()
+    t0 = time.perf_counter()
+    stack.step()
+    torch.cuda.synchronize()
+    slow = time.perf_counter() - t0
+    assert torch.equal(stack.x_states.view(torch.int16), ref.view(torch.int16))
+    assert slow > plain + 4 * 1.5e-3 and slow < plain + 4 * 4e-3, (plain, slow)   # 4 blocks x 2 ms, and it does end
+    with pytest.raises(B.PgmoeError):
+        stack.ctx.set_nonmoe_standin(-1.0)
+    stack.ctx.set_nonmoe_standin(0.0)
+    stack.close()
+
+
 # ------------------------------------------------------------------------------ migration engine
 def _device_bytes(addr, nbytes):
     """Copy nbytes from a raw device address to host (plumbing: hipMemcpy through ctypes)."""
