@@ -225,7 +225,7 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
                       "mean_unique_experts_per_block": float(uniq.mean())},
     }
 
-    if out["roofline"]["kernel"] == "ffn_gemm_kernel":
+    if out["roofline"]["kernel"].startswith("ffn_gemm"):
         # hundreds of rows per expert: the two tiled GEMMs are bound by the matrix cores, not by
         # HBM (arithmetic intensity = rows per expert); the timed region spans both GEMM kernels
         flops = 4.0 * T * k * w.d_model * w.d_ff

@@ -228,6 +228,7 @@ FFN_CASES = [
     # hundreds of rows per expert: the two tiled GEMMs (ragged 256-row chunks, an idle expert, a 5-row expert)
     ("bf16", 768, 3072, 2, [300, 217]),
     ("bf16", 256, 512, 3, [0, 700, 5]),
+    ("bf16", 512, 1024, 4, [600, 700, 500, 760]),              # enough row chunks for two K slices instead of four
 ]
 
 
