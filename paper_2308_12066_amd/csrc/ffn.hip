@@ -379,7 +379,9 @@ __global__ __launch_bounds__(256) void ffn_decode_kernel(
 //    the CUs per product and L2 misses on about a quarter of it (per XCD one expert's weights
 //    and rows, 7.8 MB, against 4 MB of L2).  Neither a deeper ring (3 to 8 stages), nor more
 //    workgroups per CU, nor reading fragments a stage ahead, nor K slices, nor k orders rotated
-//    per expert / per column block (memory channels) move it by more than a tenth;
+//    per expert / per column block (memory channels) move it by more than a tenth; a fifth
+//    wavefront that touches the lines 8 to 24 stages ahead (to have them in L2) makes it slower
+//    (55 us: it has to join every barrier, and the workgroup then waits for its loads too);
 //  * 256 x 256 tiles with eight wavefronts halve that traffic and reach 32 us for the down
 //    product, but need 256-row chunks, with which the up product is slower; not kept;
 //  * for the up product the same direct loads are slower (44 us) than staging through registers:

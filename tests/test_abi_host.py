@@ -132,6 +132,17 @@ def test_pack_is_the_documented_permutation_and_unpack_inverts_it(d, f):
     assert np.array_equal(u1, w1) and np.array_equal(u2, w2)
 
 
+def test_nonmoe_standin_setter_validates_its_argument():
+    c = B.Context(cfg())
+    c.set_nonmoe_standin(0.0)
+    c.set_nonmoe_standin(250.0)
+    for bad in (-1.0, 100001.0, float("nan"), float("inf")):
+        with pytest.raises(B.PgmoeError) as ei:
+            c.set_nonmoe_standin(bad)
+        assert ei.value.code == B.EINVAL and "outside" in str(ei.value)
+    c.close()
+
+
 def test_pack_f32_is_plain_concatenation():
     c = cfg(d_model=6, d_ff=10, dtype=B.F32)
     g = np.random.default_rng(0)
