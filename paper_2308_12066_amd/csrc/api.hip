@@ -207,9 +207,11 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
             hipEvent_t **arrays[] = {&c->fetch_begin, &c->fetch_end, &c->ev_c0, &c->ev_ready, &c->ev_waited, &c->ev_c1};
             for (hipEvent_t **a : arrays) {
                 *a = new (std::nothrow) hipEvent_t[cfg->n_blocks]();
+                if (!*a && rc == PGMOE_OK) rc = fail(nullptr, PGMOE_EINVAL, "pgmoe_create: out of host memory");
                 for (int b = 0; b < cfg->n_blocks && rc == PGMOE_OK; ++b) H(hipEventCreate(&(*a)[b]), "hipEventCreate");
             }
             c->traced = new (std::nothrow) bool[cfg->n_blocks]();
+            if (!c->traced && rc == PGMOE_OK) rc = fail(nullptr, PGMOE_EINVAL, "pgmoe_create: out of host memory");
         }
         if (rc != PGMOE_OK) {
             pgmoe_destroy(c);
