@@ -782,13 +782,7 @@ static int smallest_divisor_at_least(int n, int want) {
     return n;
 }
 
-static int env_int(const char *name, int dflt) {
-    const char *v = getenv(name);
-    return v && *v ? atoi(v) : dflt;
-}
-
-// Geometry of the fused kernel for n_rows rows.  Developer overrides (for sweeps): environment
-// variables PGMOE_FFN_MT, PGMOE_FFN_NW, PGMOE_FFN_P, read at every call.
+// Geometry of the fused kernel for n_rows rows, from the shape of the launch alone.
 FfnPlan plan_ffn(const pgmoe_config &c, int n_rows) {
     FfnPlan p;
     const int E = c.n_experts;
@@ -804,8 +798,6 @@ FfnPlan plan_ffn(const pgmoe_config &c, int n_rows) {
     if (mt == 4 && (kt == 24 || kt == 32)) nw = 8;
     if (mt == 4 && nw == 4 && kt > 24) mt = 2;
     if (mt == 2 && kt > 32) mt = 1;
-    mt = env_int("PGMOE_FFN_MT", mt);
-    nw = env_int("PGMOE_FFN_NW", nw);
     p.mt = mt;
     p.nw = nw;
     p.max_chunks = active + n_rows / (16 * mt);
@@ -816,7 +808,6 @@ FfnPlan plan_ffn(const pgmoe_config &c, int n_rows) {
     int want = (768 + active - 1) / active;
     const double traffic_cap = 0.06 * (double)active * c.d_ff / (2.0 * n_rows);
     want = std::max(1, std::min(want, (int)traffic_cap));
-    want = env_int("PGMOE_FFN_P", want);
     p.n_partial = smallest_divisor_at_least(nsub, std::min(want, nsub));
     p.f_range = c.d_ff / p.n_partial;
     return p;
