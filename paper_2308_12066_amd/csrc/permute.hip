@@ -4,10 +4,13 @@
 // step skips the gather: route_kernel also writes the inverse map (grouped row -> token) and the
 // expert kernels read their rows through it.
 //
-// route_kernel: one workgroup of 1024 threads (16 wavefronts).  Pass 1 counts with LDS
-// atomics (integer, so order does not matter).  Pass 2 walks the entries in order, 1024 at
-// a time; inside a wavefront equal keys find each other with one ballot per key bit, and a
-// per-wavefront count table turns that into a stable rank.  Everything is integer work and
+// route_kernel: one workgroup of 1024 threads; each of its 16 wavefronts owns one contiguous
+// range of the entries.  Pass 1 counts every range into a histogram of its own (LDS atomics:
+// integer, so order does not matter).  One thread per expert then turns the 16 histograms into
+// the start of every (wavefront, expert) run, and one wavefront scans the expert totals.  Pass 2
+// needs no further workgroup barrier: a wavefront walks its range in order, 64 entries at a time;
+// equal keys find each other with one ballot per key bit, which gives the stable rank inside the
+// 64, and the run's start moves on by the number of matches.  Everything is integer work and
 // bit-reproducible.
 // gather_rows_kernel: one wavefront per entry, 16-byte copies.
 #include "pgmoe_internal.h"
@@ -21,58 +24,82 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(const int32_t *__r
                                                                int32_t *__restrict__ row_of,
                                                                int32_t *__restrict__ offsets,
                                                                int32_t *__restrict__ src_row, uint32_t *flags) {
-    __shared__ int cnt[PGMOE_MAX_EXPERTS];
-    __shared__ int scan[PGMOE_MAX_EXPERTS];
-    __shared__ int base[PGMOE_MAX_EXPERTS];
-    __shared__ int whist[ROUTE_WAVES][PGMOE_MAX_EXPERTS];
-    __shared__ int wbase[ROUTE_WAVES][PGMOE_MAX_EXPERTS];
+    __shared__ int run_start[ROUTE_WAVES][PGMOE_MAX_EXPERTS];  // pass 1: counts; then: next free row of the (wavefront, expert) run
+    __shared__ int total[PGMOE_MAX_EXPERTS];                    // entries per expert, then the expert's first row
+    static_assert(PGMOE_MAX_EXPERTS == 256, "four experts per lane in the scan below");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid; i < PGMOE_MAX_EXPERTS; i += ROUTE_THREADS) cnt[i] = 0;
-    for (int i = tid; i < ROUTE_WAVES * PGMOE_MAX_EXPERTS; i += ROUTE_THREADS) (&whist[0][0])[i] = 0;
+    const int per = ((n + ROUTE_WAVES - 1) / ROUTE_WAVES + 63) & ~63;  // entries per wavefront, whole rounds of 64
+    const int lo = min(n, wave * per), hi = min(n, lo + per);
+    for (int i = tid; i < ROUTE_WAVES * PGMOE_MAX_EXPERTS; i += ROUTE_THREADS) (&run_start[0][0])[i] = 0;
     __syncthreads();
 
+    // the first ROUTE_KEEP rounds of a wavefront's range stay in registers for pass 2 (all of them up to
+    // 8192 entries), and their loads are in flight together
+    constexpr int ROUTE_KEEP = 8;
+    int kept[ROUTE_KEEP];
+#pragma unroll
+    for (int c = 0; c < ROUTE_KEEP; ++c) {
+        const int i = lo + c * 64 + lane;
+        kept[c] = i < hi ? idx[i] : 0;
+    }
     bool bad = false;
-    for (int i = tid; i < n; i += ROUTE_THREADS) {
+#pragma unroll
+    for (int c = 0; c < ROUTE_KEEP; ++c) {
+        const int i = lo + c * 64 + lane;
+        if (kept[c] < 0 || kept[c] >= E) {
+            bad = true;
+            kept[c] = kept[c] < 0 ? 0 : E - 1;
+        }
+        if (i < hi) atomicAdd(&run_start[wave][kept[c]], 1);
+    }
+    for (int i = lo + ROUTE_KEEP * 64 + lane; i < hi; i += 64) {
         int e = idx[i];
         if (e < 0 || e >= E) {
             bad = true;
             e = e < 0 ? 0 : E - 1;
         }
-        atomicAdd(&cnt[e], 1);
+        atomicAdd(&run_start[wave][e], 1);
     }
     if (__any(bad) && lane == 0) atomicOr(flags, kFlagBadIndex);
     __syncthreads();
 
-    // exclusive scan of cnt[0..E) (E <= 256): Hillis-Steele on the first 256 threads
-    if (tid < PGMOE_MAX_EXPERTS) scan[tid] = tid < E ? cnt[tid] : 0;
+    // per expert: counts of the wavefronts -> offsets of their runs inside the expert's group
+    if (tid < PGMOE_MAX_EXPERTS) {
+        int run = 0;
+        if (tid < E)
+            for (int w = 0; w < ROUTE_WAVES; ++w) {
+                const int c = run_start[w][tid];
+                run_start[w][tid] = run;
+                run += c;
+            }
+        total[tid] = run;
+    }
     __syncthreads();
-    for (int off = 1; off < PGMOE_MAX_EXPERTS; off <<= 1) {
-        int v = 0;
-        if (tid < PGMOE_MAX_EXPERTS && tid >= off) v = scan[tid - off];
-        __syncthreads();
-        if (tid < PGMOE_MAX_EXPERTS) scan[tid] += v;
-        __syncthreads();
+    // exclusive scan of the expert totals by the first wavefront, four experts per lane
+    if (wave == 0) {
+        const int t0 = total[4 * lane], t1 = total[4 * lane + 1], t2 = total[4 * lane + 2], t3 = total[4 * lane + 3];
+        int incl = t0 + t1 + t2 + t3;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(incl, off);
+            if (lane >= off) incl += o;
+        }
+        const int first[4] = {incl - (t0 + t1 + t2 + t3), incl - (t1 + t2 + t3), incl - (t2 + t3), incl - t3};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = 4 * lane + j;
+            total[e] = first[j];
+            if (e < E) offsets[e] = first[j];
+        }
+        if (lane == 0) offsets[E] = n;
     }
-    if (tid < E) {
-        const int excl = scan[tid] - cnt[tid];
-        base[tid] = excl;
-        offsets[tid] = excl;
-    }
-    if (tid == 0) offsets[E] = n;
     __syncthreads();
 
     int nbits = 0;
     while ((1 << nbits) < E) ++nbits;
-
-    for (int c0 = 0; c0 < n; c0 += ROUTE_THREADS) {
-        const int i = c0 + tid;
-        const bool valid = i < n;
-        int e = 0;
-        if (valid) {
-            e = idx[i];
-            e = e < 0 ? 0 : (e >= E ? E - 1 : e);
-        }
+    volatile int *my_run = run_start[wave];  // shared by the lanes of this wavefront only, which run in lockstep
+    auto place = [&](int i, bool valid, int e) {
         unsigned long long peers = __ballot(valid);
         for (int b = 0; b < nbits; ++b) {
             const bool bit = (e >> b) & 1;
@@ -80,26 +107,31 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(const int32_t *__r
             peers &= bit ? m : ~m;
         }
         const unsigned long long below = (1ull << lane) - 1ull;
-        const int rank_in_wave = __popcll(peers & below);
-        const bool leader = valid && rank_in_wave == 0;
-        if (leader) whist[wave][e] = __popcll(peers);
-        __syncthreads();
-        if (tid < E) {
-            int run = base[tid];
-            for (int w = 0; w < ROUTE_WAVES; ++w) {
-                wbase[w][tid] = run;
-                run += whist[w][tid];
-            }
-            base[tid] = run;
-        }
-        __syncthreads();
+        const int rank_in_round = __popcll(peers & below);
+        const int start = my_run[e];       // every lane reads before the leaders write
+        __builtin_amdgcn_wave_barrier();
+        if (valid && rank_in_round == 0) my_run[e] = start + __popcll(peers);
+        __builtin_amdgcn_wave_barrier();
         if (valid) {
-            const int r = wbase[wave][e] + rank_in_wave;
+            const int r = total[e] + start + rank_in_round;
             row_of[i] = r;
             if (src_row) src_row[r] = i / k;  // the inverse map: which token's row sits in grouped row r
         }
-        if (leader) whist[wave][e] = 0;
-        __syncthreads();
+    };
+#pragma unroll
+    for (int c = 0; c < ROUTE_KEEP; ++c) {
+        const int i = lo + c * 64 + lane;
+        if (lo + c * 64 < hi) place(i, i < hi, kept[c]);  // uniform over the wavefront
+    }
+    for (int c0 = lo + ROUTE_KEEP * 64; c0 < hi; c0 += 64) {
+        const int i = c0 + lane;
+        const bool valid = i < hi;
+        int e = 0;
+        if (valid) {
+            e = idx[i];
+            e = e < 0 ? 0 : (e >= E ? E - 1 : e);
+        }
+        place(i, valid, e);
     }
 }
 

@@ -120,6 +120,7 @@ def test_gate_ties_go_to_lowest_index_and_nan_is_flagged(hx):
     ("f32", 32, 64, 8, 1, "rand"), ("bf16", 1, 768, 8, 1, "rand"), ("bf16", 64, 1024, 128, 2, "rand"),
     ("bf16", 4096, 768, 128, 1, "rand"), ("bf16", 1500, 64, 7, 3, "rand"), ("bf16", 1111, 64, 256, 1, "one"),
     ("f32", 3, 5, 4, 4, "rand"), ("bf16", 2500, 128, 64, 2, "zipf"),
+    ("bf16", 6000, 64, 33, 2, "zipf"),      # 12000 entries: more rounds per wavefront than the grouping kernel keeps in registers
 ])
 def test_permute_is_bit_exact(hx, dtype, T, d, E, k, mode):
     H, B = hx
