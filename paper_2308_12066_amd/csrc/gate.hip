@@ -46,9 +46,9 @@ __device__ inline void softmax_topk(const float *zs, int zstride, int t0, int nt
                                     float *__restrict__ probs_out, uint32_t *flags,
                                     int32_t *idx_lds = nullptr) {  // nullable: LDS copy [nt*k] of the chosen indices
     const int tid = threadIdx.x;
-    const int sub = tid & 15, grp = tid >> 4;  // 16 groups per 256-thread workgroup
+    const int sub = tid & 15, grp = tid >> 4;  // 16 lanes per group
     bool any_nan = false;
-    for (int tb = 0; tb < nt; tb += GATE_THREADS / 16) {  // uniform trip count; idle groups just skip the writes
+    for (int tb = 0; tb < nt; tb += (int)blockDim.x / 16) {  // uniform trip count; idle groups just skip the writes
         const int t = tb + grp;
         const bool live = t < nt;
         float v[16];
@@ -232,9 +232,9 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_vec_kernel(
 }
 
 // Matrix-core path (bf16, E a multiple of 8, d_model a multiple of 32): the gate is a skinny
-// GEMM [T,d] x [d,E].  A workgroup takes 16 tokens (one matrix-core tile); its four wavefronts
-// split the d_model reduction (k-tile kt goes to wavefront kt % 4) and their partial logits are
-// added in LDS in wavefront order.  Nothing is staged through LDS on the way in:
+// GEMM [T,d] x [d,E].  A workgroup takes 16 tokens (one matrix-core tile); its NW wavefronts
+// (eight for E <= 128, four above) split the d_model reduction (k-tile kt goes to wavefront
+// kt % NW) and their partial logits are added in LDS in wavefront order.  Nothing is staged through LDS on the way in:
 //   * the token operand (16 tokens x 32 k) is one 16-byte load per lane straight from x;
 //   * W is row-major [d,E], an expert's weights are strided, but lane (n, g) can load rows
 //     32*kt + 8*g .. +7 of the eight experts 8*n .. 8*n+7 with eight contiguous 16-byte loads and
@@ -247,8 +247,8 @@ typedef float gfloatx4 __attribute__((ext_vector_type(4)));
 constexpr int GM_TOK = 16;  // tokens per workgroup
 constexpr int GATE_ROUTE_MAX = 256;  // most (token, choice) pairs the gate kernel groups by itself
 
-template <int NP>  // passes of 128 experts (1: E <= 128, 2: E <= 256)
-__global__ __launch_bounds__(GATE_THREADS) void gate_topk_mfma_kernel(
+template <int NP, int NW>  // NP: passes of 128 experts (1: E <= 128, 2: E <= 256); NW: wavefronts that split d_model
+__global__ __launch_bounds__(NW * 64) void gate_topk_mfma_kernel(
     const __bf16 *__restrict__ x, const __bf16 *__restrict__ w, const float *__restrict__ bias, int T, int d, int E, int k,
     int32_t *__restrict__ idx_out, float *__restrict__ prob_out, float *__restrict__ probs_out, uint32_t *flags,
     int32_t *__restrict__ row_of, int32_t *__restrict__ offsets, int32_t *__restrict__ src_row) {  // routing outputs: see below
@@ -260,8 +260,9 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_mfma_kernel(
     const int KT = d >> 5;
     const int ncv = E >> 3;           // 8-expert column vectors per W row
     const int ecols = NP * 128;       // logit columns kept per token in LDS
-    float *part = reinterpret_cast<float *>(gsm);            // [4][GM_TOK][ecols]
-    float *zs = part + 4 * GM_TOK * ecols;                   // [GM_TOK][ecols]
+    constexpr int NT = NW * 64;                              // threads
+    float *part = reinterpret_cast<float *>(gsm);            // [NW][GM_TOK][ecols]
+    float *zs = part + NW * GM_TOK * ecols;                  // [GM_TOK][ecols]
 
     gfloatx4 acc[NP][8];
 #pragma unroll
@@ -294,8 +295,8 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_mfma_kernel(
         }
     };
 #pragma unroll
-    for (int st = 0; st < PF; ++st) request(wave + 4 * st, a_buf[st], rows_buf[st]);
-    for (int kt0 = wave; kt0 < KT; kt0 += 4 * PF) {
+    for (int st = 0; st < PF; ++st) request(wave + NW * st, a_buf[st], rows_buf[st]);
+    for (int kt0 = wave; kt0 < KT; kt0 += NW * PF) {
 #pragma unroll
         for (int st = 0; st < PF; ++st) {
             const gbf16x8 a = a_buf[st];
@@ -306,7 +307,7 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_mfma_kernel(
                 for (int q = 0; q < 8; ++q)
 #pragma unroll
                     for (int j = 0; j < 8; ++j) cells[p][q][j] = rows_buf[st][p][j][q];
-            request(kt0 + 4 * (st + PF), a_buf[st], rows_buf[st]);
+            request(kt0 + NW * (st + PF), a_buf[st], rows_buf[st]);
 #pragma unroll
             for (int p = 0; p < NP; ++p)
 #pragma unroll
@@ -329,10 +330,12 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_mfma_kernel(
         }
     __syncthreads();
     constexpr int PLANE = NP * 8 * 4 * 64;  // floats per wavefront
-    for (int o = tid; o < PLANE; o += GATE_THREADS) {
+    for (int o = tid; o < PLANE; o += NT) {
         const int l = o & 63, r = (o >> 6) & 3, q = (o >> 8) & 7, p = o >> 11;
         const int e = 8 * ((l & 15) + 16 * p) + q, tokl = 4 * (l >> 4) + r;
-        const float sum = ((part[o] + part[PLANE + o]) + part[2 * PLANE + o]) + part[3 * PLANE + o];
+        float sum = part[o];
+#pragma unroll
+        for (int wv = 1; wv < NW; ++wv) sum += part[wv * PLANE + o];
         zs[tokl * ecols + e] = sum + ((bias && e < E) ? bias[e] : 0.f);
     }
     __syncthreads();
@@ -347,13 +350,13 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_mfma_kernel(
     if (!route) return;
     const int n_sel = nt * k;
     __syncthreads();
-    for (int e = tid; e < E; e += GATE_THREADS) {
+    for (int e = tid; e < E; e += NT) {
         int c = 0;
         for (int i = 0; i < n_sel; ++i) c += r_idx[i] == e ? 1 : 0;
         r_cnt[e] = c;
     }
     __syncthreads();
-    for (int e = tid; e < E; e += GATE_THREADS) {
+    for (int e = tid; e < E; e += NT) {
         int o = 0;
         for (int q = 0; q < e; ++q) o += r_cnt[q];
         r_off[e] = o;
@@ -361,7 +364,7 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_mfma_kernel(
     }
     if (tid == 0) offsets[E] = n_sel;
     __syncthreads();
-    for (int i = tid; i < n_sel; i += GATE_THREADS) {
+    for (int i = tid; i < n_sel; i += NT) {
         const int e = r_idx[i];
         int rank = 0;
         for (int q = 0; q < i; ++q) rank += r_idx[q] == e ? 1 : 0;
@@ -397,25 +400,28 @@ static int launch_gate_mfma(pgmoe_ctx *ctx, const __bf16 *x, const __bf16 *w, co
                             bool *routed) {
     const pgmoe_config &c = ctx->cfg;
     const int np = c.n_experts <= 128 ? 1 : 2;
-    const size_t lds = (size_t)5 * GM_TOK * np * 128 * sizeof(float);  // 4 partial planes + the logits
     const dim3 grid((T + GM_TOK - 1) / GM_TOK);
     // grouping inside the gate kernel: one workgroup holds the whole batch and the selections fit
     const bool route = row_of && offsets && src_row && grid.x == 1 && T * c.top_k <= GATE_ROUTE_MAX;
     if (!route) row_of = offsets = src_row = nullptr;
     if (routed) *routed = route;
-    if (np == 1) {
-        hipLaunchKernelGGL(gate_topk_mfma_kernel<1>, grid, dim3(GATE_THREADS), lds, s, x, w, bias, T, c.d_model, c.n_experts,
-                           c.top_k, idx, prob, probs, ctx->dev_flags, row_of, offsets, src_row);
-    } else {
-        auto kern = gate_topk_mfma_kernel<2>;
-        static thread_local bool attr_set = false;
-        if (!attr_set) {
-            PG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            attr_set = true;
-        }
-        hipLaunchKernelGGL(kern, grid, dim3(GATE_THREADS), lds, s, x, w, bias, T, c.d_model, c.n_experts, c.top_k, idx, prob,
-                           probs, ctx->dev_flags, row_of, offsets, src_row);
-    }
+    // eight wavefronts split d_model: with a three-deep prefetch ring each of them has all its
+    // k-tiles (d_model <= 768) in flight at once, i.e. the kernel pays the memory latency once
+#define PG_GATE_MFMA(NP_, NW_)                                                                                          \
+    do {                                                                                                                \
+        auto kern = gate_topk_mfma_kernel<NP_, NW_>;                                                                    \
+        const size_t lds = (size_t)(NW_ + 1) * GM_TOK * NP_ * 128 * sizeof(float); /* NW partial planes + the logits */ \
+        static thread_local bool attr_set = false;                                                                      \
+        if (lds > 48 * 1024 && !attr_set) {                                                                             \
+            PG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+            attr_set = true;                                                                                            \
+        }                                                                                                               \
+        hipLaunchKernelGGL(kern, grid, dim3(NW_ * 64), lds, s, x, w, bias, T, c.d_model, c.n_experts, c.top_k, idx, prob, probs, \
+                           ctx->dev_flags, row_of, offsets, src_row);                                                   \
+    } while (0)
+    if (np == 1) PG_GATE_MFMA(1, 8);
+    else PG_GATE_MFMA(2, 4);
+#undef PG_GATE_MFMA
     PG_HIP(ctx, hipGetLastError());
     return PGMOE_OK;
 }
