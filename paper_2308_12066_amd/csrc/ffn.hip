@@ -383,7 +383,11 @@ __global__ __launch_bounds__(256) void ffn_decode_kernel(
 //    wavefront that touches the lines 8 to 24 stages ahead (to have them in L2) makes it slower
 //    (55 us: it has to join every barrier, and the workgroup then waits for its loads too);
 //  * 256 x 256 tiles with eight wavefronts halve that traffic and reach 32 us for the down
-//    product, but need 256-row chunks, with which the up product is slower; not kept;
+//    product, but need 256-row chunks, with which the up product is slower; not kept.  The same
+//    tile with four wavefronts of 128 x 128 (sixteen 32x32x16 accumulators each, pinned to the
+//    accumulation registers from inline assembly, whose last product per accumulator must carry
+//    its own wait states because the compiler reads "finished" accumulators at once) is correct
+//    but slower still, 40 us: with one wavefront per SIMD every wait is exposed;
 //  * for the up product the same direct loads are slower (44 us) than staging through registers:
 //    x is row-major, an operand tile then takes 16 bytes from each of 16 rows per lane group
 //    and the address unit, not the data, paces the load.  Variants of the register-staged kernel
