@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpgmoe.so")
-SOURCES = ["api.hip", "gate.hip", "permute.hip", "ffn.hip", "combine.hip", "fetch.hip", "engine.hip"]
+SOURCES = ["api.hip", "gate.hip", "permute.hip", "ffn.hip", "ffn_gemm.hip", "combine.hip", "fetch.hip", "engine.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -34,7 +34,7 @@ FLAGS = [
 def _compile(src: str, force: bool) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
     path = os.path.join(CSRC, src)
-    deps = [path, os.path.join(CSRC, "pgmoe_internal.h"), os.path.join(ROOT, "include", "pgmoe.h")]
+    deps = [path, os.path.join(CSRC, "pgmoe_internal.h"), os.path.join(CSRC, "ffn_common.h"), os.path.join(ROOT, "include", "pgmoe.h")]
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
     subprocess.run([HIPCC, *FLAGS, "-c", path, "-o", obj], check=True)

@@ -1,5 +1,5 @@
 // libpgmoe: context, argument validation, host-side helpers and the exported entry points of
-// the single operations.  Kernels live in gate.hip, permute.hip, ffn.hip, combine.hip; the
+// the single operations.  Kernels live in gate.hip, permute.hip, ffn.hip, ffn_gemm.hip, combine.hip; the
 // migration engine and the whole-stack step in engine.hip.
 #include <algorithm>
 #include <new>
