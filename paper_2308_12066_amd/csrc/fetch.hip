@@ -8,7 +8,9 @@
 // 16-byte loads over the host link.  Host-link reads in flight slow down every concurrent HBM
 // access on this chip (a 9.4 MB read kernel goes from 2.9 us to 7/9/12/30 us with 64/96/128/512
 // KiB of pull loads outstanding), so the grid keeps just enough in flight to saturate the link:
-// 24 workgroups x 4 wavefronts x one 1 KiB load each (96 KiB: 56.3 of 57 GB/s).
+// 24 workgroups x 4 wavefronts x one 1 KiB load each (96 KiB: 56.3 of 57 GB/s).  The slowdown is
+// not confined to the XCD the loads come from: with all 24 workgroups placed on one XCD the
+// concurrent FFN is slower still (14.6 instead of 11.6 us) and so is the link (50 instead of 52 GB/s).
 #include "pgmoe_internal.h"
 
 namespace pgmoe {
