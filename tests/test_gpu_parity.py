@@ -230,6 +230,7 @@ FFN_CASES = [
     ("bf16", 768, 3072, 2, [300, 217]),
     ("bf16", 256, 512, 3, [0, 700, 5]),
     ("bf16", 512, 1024, 4, [600, 700, 500, 760]),              # enough row chunks for two K slices instead of four
+    ("bf16", 1024, 4096, 2, [333, 290]),                       # the two GEMMs on the Switch-Large expert shape
 ]
 
 
@@ -652,15 +653,21 @@ def test_comparison_schedules_match_the_conventional_oracle(hx, schedule, fetch,
 
 
 # ------------------------------------------------------------------------------ expert cache
-@pytest.mark.parametrize("policy", ["lru", "lfu", "lifo"])
-def test_expert_cache_changes_the_copies_not_the_results(hx, policy):
+@pytest.mark.parametrize("policy,shape", [("lru", "decode"), ("lfu", "decode"), ("lifo", "decode"), ("lru", "gemm")])
+def test_expert_cache_changes_the_copies_not_the_results(hx, policy, shape):
     """A stack with an expert cache gives bit-identical hidden states to the same stack without
-    one, and the device's hit / copy counts equal the reference model of the policy."""
+    one, and the device's hit / copy counts equal the reference model of the policy.  The "gemm"
+    shape sends 256 rows to each expert, so the two tiled GEMM kernels find their weights through
+    the cache's pointer table too."""
     from oracle.cache_policy import ExpertCache, LRU, LFU, LIFO
     H, B = hx
     pol = {"lru": (B.CACHE_LRU, LRU), "lfu": (B.CACHE_LFU, LFU), "lifo": (B.CACHE_LIFO, LIFO)}[policy]
-    w = W.Workload("cache_case", 95, 4, 256, 512, 32, 2, 12, 1, "bf16", 1.1, True)
-    C = 6
+    if shape == "decode":
+        w = W.Workload("cache_case", 95, 4, 256, 512, 32, 2, 12, 1, "bf16", 1.1, True)
+        C = 6
+    else:
+        w = W.Workload("cache_gemm_case", 96, 3, 256, 512, 4, 1, 1024, 1, "bf16", 0.0, True)
+        C = 2
     cfg = H.config_for(w)
     store = H.ExpertStore(w, cfg, threads=4)
     gates = W.gate_tensors(w)
@@ -668,7 +675,9 @@ def test_expert_cache_changes_the_copies_not_the_results(hx, policy):
     cached = H.Stack(w, store, gates=gates, cache_slots=C, cache_policy=pol[0])
     models = [ExpertCache(C, pol[1]) for _ in range(w.n_blocks)]
     hits_total = 0
-    for s in range(10):
+    if shape == "gemm":
+        assert "gemm" in cached.ctx.ffn_kernel_name(w.tokens * w.top_k)
+    for s in range(10 if shape == "decode" else 4):
         x0 = W.step_input(w, s)
         for st in (plain, cached):
             st.set_input(x0)
