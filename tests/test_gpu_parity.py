@@ -537,11 +537,21 @@ def test_fetch_copies_exactly_the_selected_experts(hx, fetch):
     ctx.close()
 
 
-def test_pull_fetch_with_too_few_slots_flags_and_zeroes(hx):
+@pytest.mark.parametrize("shape", ["decode", "gemm"])
+def test_pull_fetch_with_too_few_slots_flags_and_zeroes(hx, shape):
     """slots_per_gen smaller than the number of distinct experts: the pull kernel copies the
-    first slots_per_gen experts, raises the device flag, and the FFN zeroes the other rows."""
+    first slots_per_gen experts, raises the device flag, and the FFN zeroes the other rows
+    (fused kernel for the decode shape, the two tiled GEMMs for 250 rows per expert)."""
     H, B = hx
-    w = W.Workload("noslot_case", 71, 1, 128, 256, 8, 1, 8, 1, "bf16", 0.0, True)
+    if shape == "decode":
+        w = W.Workload("noslot_case", 71, 1, 128, 256, 8, 1, 8, 1, "bf16", 0.0, True)
+        idx = np.array([[1], [1], [3], [5], [5], [6], [3], [1]], dtype=np.int32)      # distinct: 1, 3, 5, 6
+        kept, dropped = (1, 3), (5, 6)
+    else:
+        w = W.Workload("noslot_gemm_case", 72, 1, 128, 256, 4, 1, 1000, 1, "bf16", 0.0, True)
+        idx = np.random.default_rng(9).permutation(np.repeat(np.arange(4, dtype=np.int32), 250)).reshape(-1, 1)
+        kept, dropped = (0, 1), (2, 3)
+    T, E = w.tokens, w.n_experts
     cfg = H.config_for(w, slots_per_gen=2)
     cache = {}
 
@@ -553,27 +563,27 @@ def test_pull_fetch_with_too_few_slots_flags_and_zeroes(hx):
     ctx = B.Context(cfg)
     ctx.register_host_experts(store.host, store.expert_stride, store.block_stride)
     comp, copy = torch.cuda.Stream(), torch.cuda.Stream()
-    idx = np.array([[1], [1], [3], [5], [5], [6], [3], [1]], dtype=np.int32)      # distinct: 1, 3, 5, 6
-    x = W.round_to_bf16(np.random.default_rng(2).standard_normal((8, 128)).astype(np.float32))
+    x = W.round_to_bf16(np.random.default_rng(2).standard_normal((T, 128)).astype(np.float32))
     xd, idx_d = H.to_device(x, "bf16"), torch.from_numpy(idx).cuda()
-    x_perm = torch.zeros((8, 128), dtype=torch.bfloat16, device="cuda")
-    y_perm = torch.full((8, 128), 3.0, dtype=torch.bfloat16, device="cuda")
-    row_of = torch.zeros(8, dtype=torch.int32, device="cuda")
-    offs = torch.zeros(9, dtype=torch.int32, device="cuda")
+    x_perm = torch.zeros((T, 128), dtype=torch.bfloat16, device="cuda")
+    y_perm = torch.full((T, 128), 3.0, dtype=torch.bfloat16, device="cuda")
+    row_of = torch.zeros(T, dtype=torch.int32, device="cuda")
+    offs = torch.zeros(E + 1, dtype=torch.int32, device="cuda")
     ws = torch.zeros(ctx.workspace_bytes, dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
-    assert ctx.fetch_experts(0, idx_d, 8, comp, copy) == 4
-    ctx.permute(xd, idx_d, 8, x_perm, row_of, offs, comp)
-    ctx.expert_ffn(0, x_perm, offs, 8, y_perm, ws, comp)
+    assert ("gemm" in ctx.ffn_kernel_name(T)) == (shape == "gemm")
+    assert ctx.fetch_experts(0, idx_d, T, comp, copy) == 4
+    ctx.permute(xd, idx_d, T, x_perm, row_of, offs, comp)
+    ctx.expert_ffn(0, x_perm, offs, T, y_perm, ws, comp)
     torch.cuda.synchronize()
     assert ctx.device_flags() & 4
-    r = R.route(idx, 8)
+    r = R.route(idx, E)
     y = H.to_numpy64(y_perm)
-    for e in (1, 3):
+    for e in kept:
         rows = slice(r["offsets"][e], r["offsets"][e + 1])
         ref = R.ffn_rows(x[idx[:, 0] == e], *cache[e])
         assert nerr(y[rows], ref) <= TOL["bf16"]
-    for e in (5, 6):
+    for e in dropped:
         assert np.all(y[r["offsets"][e]: r["offsets"][e + 1]] == 0.0)
     ctx.close()
 
