@@ -249,6 +249,41 @@ def test_expert_ffn_matches_oracle(hx, dtype, d, f, E, counts):
             assert nerr(out[offs[e]: offs[e + 1]], ref[offs[e]: offs[e + 1]]) <= TOL[dtype], f"expert {e}"
 
 
+@pytest.mark.parametrize("d,f,E,counts", [
+    (768, 3072, 4, [300, 217, 512, 200]),     # the two tiled GEMMs (LDS ring filled by direct loads)
+    (768, 3072, 16, [40, 25, 33, 64, 7, 0, 16, 12, 3, 50, 9, 1, 0, 30, 22, 18]),   # fused kernel
+    (768, 3072, 8, [0, 0, 1, 0, 0, 2, 0, 0]),  # decode kernel
+])
+def test_expert_ffn_is_bit_reproducible_run_after_run(hx, d, f, E, counts):
+    """The kernels add in a fixed order and use no atomics on floats, so repeating a launch must give
+    the same bits; a race in an LDS ring or a missed wait would show up here as a difference."""
+    H, B = hx
+    n = int(sum(counts))
+    w = W.Workload("ffn_repeat_case", 51, 1, d, f, E, 1, n, 1, "bf16", 0.0, False)
+    cfg = H.config_for(w)
+    g = np.random.default_rng(d + E)
+    store = H.ExpertStore(w, cfg, threads=4, get_expert=lambda b, e: (
+        W.round_to_bf16((np.random.default_rng(1000 + e).standard_normal((d, f)) * 0.05).astype(np.float32)),
+        W.round_to_bf16((np.random.default_rng(2000 + e).standard_normal((f, d)) * 0.05).astype(np.float32))))
+    ctx = B.Context(cfg)
+    ctx.register_resident_experts(store.to_hbm(), store.expert_stride, store.block_stride)
+    xd = H.to_device(W.round_to_bf16(g.standard_normal((n, d)).astype(np.float32)), "bf16")
+    offs = torch.from_numpy(np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)).cuda()
+    ws = torch.zeros(ctx.workspace_bytes, dtype=torch.uint8, device="cuda")
+    y = torch.zeros((n, d), dtype=torch.bfloat16, device="cuda")
+    ctx.expert_ffn(0, xd, offs, n, y, ws)
+    torch.cuda.synchronize()
+    first = y.clone()
+    assert float(first.float().abs().max()) > 0
+    for rep in range(100):
+        y.fill_(3.0)
+        ctx.expert_ffn(0, xd, offs, n, y, ws)
+        if rep % 10 == 9:
+            torch.cuda.synchronize()
+            assert torch.equal(y.view(torch.int16), first.view(torch.int16)), f"repeat {rep} differs"
+    ctx.close()
+
+
 # ------------------------------------------------------------------------------ combine
 @pytest.mark.parametrize("dtype,T,d,k", [("f32", 32, 64, 1), ("f32", 5, 7, 3), ("bf16", 64, 1024, 2), ("bf16", 300, 768, 1)])
 def test_combine_matches_definition(hx, dtype, T, d, k):
