@@ -370,6 +370,39 @@ def make_stack(H, w, threads=HOST_THREADS, flags=0, pregate_distance=0, weight_s
     return stack, gates, (lambda b, e: cache[(b, e)])
 
 
+@pytest.mark.parametrize("T,E,k,fetch", [(8, 16, 2, "pull"), (1, 8, 1, "pull"), (300, 8, 1, "pull"), (8, 16, 2, "memcpy")])
+def test_offloaded_stack_repeats_bit_for_bit_over_many_steps(hx, T, E, k, fetch):
+    """300 steps that alternate between two inputs, all queued back to back: every step must give
+    the bits its input gave the first time.  A migration that overwrote slots still in use, an
+    FFN that started before its experts had arrived or a stale routing would show up here."""
+    H, B = hx
+    w = small_workload("bf16", T, 128, 256, E, k, L=4, offloaded=True, index=58)
+    stack, gates, cache = make_stack(H, w, flags=0 if fetch == "pull" else B.FLAG_FETCH_MEMCPY, weight_scale=4.0)
+    inputs = [H.to_device(W.step_input(w, s), "bf16") for s in range(2)]
+    first = []
+    for x0 in inputs:
+        stack.x_states[0].copy_(x0)
+        torch.cuda.synchronize()
+        stack.step()
+        torch.cuda.synchronize()
+        first.append((stack.x_states.clone(), stack.topk_idx.clone()))
+    assert not torch.equal(first[0][1], first[1][1]), "the two inputs should route differently"
+    cs = torch.cuda.current_stream()
+    for s in range(300):
+        want_x, want_idx = first[s & 1]
+        # the input copy and the check run on the stack's compute stream, in order with the steps
+        with torch.cuda.stream(stack.compute):
+            stack.x_states[0].copy_(inputs[s & 1], non_blocking=True)
+        stack.step()
+        if s % 25 >= 23:   # two consecutive steps (both inputs) out of every 25
+            torch.cuda.synchronize()
+            assert torch.equal(stack.topk_idx, want_idx), f"step {s}: routing differs"
+            assert torch.equal(stack.x_states.view(torch.int16), want_x.view(torch.int16)), f"step {s}: hidden states differ"
+    torch.cuda.synchronize()
+    assert stack.ctx.device_flags() == 0
+    stack.close()
+
+
 def test_cfg1_tiny_f32_stack_all_tokens(hx):
     H, B = hx
     w = W.CONFIGS["cfg1"]
