@@ -731,8 +731,9 @@ def test_comparison_schedules_match_the_conventional_oracle(hx, schedule, fetch,
 
 
 # ------------------------------------------------------------------------------ expert cache
-@pytest.mark.parametrize("policy,shape", [("lru", "decode"), ("lfu", "decode"), ("lifo", "decode"), ("lru", "gemm")])
-def test_expert_cache_changes_the_copies_not_the_results(hx, policy, shape):
+@pytest.mark.parametrize("policy,shape,distance", [("lru", "decode", 0), ("lfu", "decode", 0), ("lifo", "decode", 0),
+                                                   ("lru", "gemm", 0), ("lru", "decode", 2)])
+def test_expert_cache_changes_the_copies_not_the_results(hx, policy, shape, distance):
     """A stack with an expert cache gives bit-identical hidden states to the same stack without
     one, and the device's hit / copy counts equal the reference model of the policy.  The "gemm"
     shape sends 256 rows to each expert, so the two tiled GEMM kernels find their weights through
@@ -749,8 +750,8 @@ def test_expert_cache_changes_the_copies_not_the_results(hx, policy, shape):
     cfg = H.config_for(w)
     store = H.ExpertStore(w, cfg, threads=4)
     gates = W.gate_tensors(w)
-    plain = H.Stack(w, store, gates=gates)
-    cached = H.Stack(w, store, gates=gates, cache_slots=C, cache_policy=pol[0])
+    plain = H.Stack(w, store, gates=gates, pregate_distance=distance)
+    cached = H.Stack(w, store, gates=gates, cache_slots=C, cache_policy=pol[0], pregate_distance=distance)
     models = [ExpertCache(C, pol[1]) for _ in range(w.n_blocks)]
     hits_total = 0
     if shape == "gemm":
