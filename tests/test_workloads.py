@@ -1,5 +1,6 @@
 """The seeded input generators: determinism, storage rounding, and the Zipf recipe."""
 import numpy as np
+import pytest
 import torch
 
 import workloads as W
@@ -50,6 +51,28 @@ def test_zipf_bias_makes_the_hottest_expert_about_q1():
         assert int(share.argmax()) == int(b.argmax())
         assert abs(share.max() - q[0]) / q[0] < 0.25
     assert W.gate_bias(W.CONFIGS["cfg4"], 0) is None
+
+
+@pytest.mark.parametrize("name,L,d,f,E,k,T,steps,dtype,offloaded,expert_bytes,store_gb", [
+    ("cfg1", 2, 64, 256, 8, 1, 32, 1, "f32", False, 131072, None),
+    ("cfg2", 6, 768, 3072, 8, 1, 1, 128, "bf16", True, 9437184, 0.45),
+    ("cfg3", 6, 768, 3072, 64, 1, 16, 128, "bf16", True, 9437184, 3.62),
+    ("cfg4", 6, 768, 3072, 128, 1, 4096, 1, "bf16", False, 9437184, 7.25),
+    ("cfg4_offloaded", 6, 768, 3072, 128, 1, 4096, 1, "bf16", True, 9437184, 7.25),
+    ("cfg5", 12, 1024, 4096, 128, 1, 64, 64, "bf16", True, 16777216, 25.77),
+    ("cfg5_top2", 12, 1024, 4096, 128, 2, 64, 64, "bf16", True, 16777216, 25.77),
+])
+def test_configurations_have_the_shapes_and_sizes_of_the_switch_models(name, L, d, f, E, k, T, steps, dtype, offloaded,
+                                                                     expert_bytes, store_gb):
+    """The five benchmark configurations: shapes as listed for the Switch-Base / Switch-Large
+    variants (Sec. V, model table), expert bytes 2*d*f*sizeof(weight), expert store L*E*bytes."""
+    w = W.CONFIGS[name]
+    assert (w.n_blocks, w.d_model, w.d_ff, w.n_experts, w.top_k, w.tokens, w.steps, w.dtype, w.offloaded) == \
+           (L, d, f, E, k, T, steps, dtype, offloaded)
+    assert w.expert_bytes == expert_bytes
+    if store_gb is not None:
+        assert abs(w.n_blocks * w.n_experts * w.expert_bytes / 1e9 - store_gb) < 0.006
+    assert 4 * w.d_model * w.d_ff == {64: 65536, 768: 9437184, 1024: 16777216}[d]      # FFN flops per token and expert
 
 
 def test_gate_list_has_one_conventional_gate_and_L_minus_1_pregates():
