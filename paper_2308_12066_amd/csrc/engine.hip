@@ -133,7 +133,11 @@ static int fetch_impl(pgmoe_ctx *ctx, const char *fn, int block, bool all, const
     const int n = all ? 0 : T * ctx->cfg.top_k;
     const int gen = block % ctx->n_gen;
     const bool inline_fetch = ps == cs;  // exposed fetch on the compute stream itself: plain stream order
-    if (!inline_fetch && block > ctx->distance && ((block - ctx->distance) & 1)) ps = ctx->copy2;  // blocks 0..N queue on the caller's stream, then alternate
+    if (!inline_fetch && ctx->pull_seq >= 0) {
+        if (ctx->pull_seq & 1) ps = ctx->copy2;  // inside a step the migrations take turns on the link (fetch.hip): alternate from the first one on
+    } else if (!inline_fetch && block > ctx->distance && ((block - ctx->distance) & 1)) {
+        ps = ctx->copy2;  // blocks 0..N queue on the caller's stream, then alternate
+    }
     BlockStats &st = ctx->stats[block];
     st = BlockStats();
 
@@ -147,7 +151,8 @@ static int fetch_impl(pgmoe_ctx *ctx, const char *fn, int block, bool all, const
         rc = wait_for_last_reader(ctx, gen, cs, ps);
         if (rc) return rc;
         if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_begin[block], ps));
-        rc = launch_fetch_pull(ctx, block, all, topk_idx, n, ps);
+        const int seq = (ctx->pull_seq >= 0 && !inline_fetch) ? ctx->pull_seq++ : -1;
+        rc = launch_fetch_pull(ctx, block, all, topk_idx, n, ps, seq, seq >= 0 && seq == ctx->pull_last);
         if (rc) return rc;
         if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_end[block], ps));
         if (!inline_fetch) PG_HIP(ctx, hipEventRecord(ctx->fetch_done[gen], ps));
@@ -463,6 +468,17 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     if (ctx->host_only) return fail(ctx, PGMOE_ENODEVICE, "%s: context is host-only, nothing can be launched", fn);
     if (T == 0) return PGMOE_OK;
     for (int b = 0; b < L; ++b) ctx->routed[b] = false;
+    // the migrations of this step that run beside the compute stream (one per block in the pre-gated
+    // and the prefetch-all schedule) take turns on the host link; whatever path leaves this
+    // function, later stand-alone fetches are not part of a step
+    struct StepScope {
+        pgmoe_ctx *c;
+        ~StepScope() { c->pull_seq = c->pull_last = -1; }
+    } step_scope{ctx};
+    if (ctx->store_mode == STORE_HOST && ctx->pull && ctx->schedule != PGMOE_SCHED_ON_DEMAND && copy_stream != compute_stream) {
+        ctx->pull_seq = 0;
+        ctx->pull_last = L - 1;
+    }
 
     const size_t xbytes = (size_t)T * c.d_model * ctx->elem;
     const size_t nk = (size_t)T * c.top_k;

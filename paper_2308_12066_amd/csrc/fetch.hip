@@ -21,11 +21,51 @@ constexpr int FETCH_UNROLL = 1;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// Turn-taking on the host link.  Consecutive migrations of a stack step run on two alternating
+// streams, so that the next one is already resident when the current one ends and the link never
+// idles at the hand-over; left alone, the two kernels would share the link while they overlap,
+// which delays the EARLIER one: its block starts later, the pre-gate behind that block issues
+// the fetch after next later, and the link idles there instead (17-23 us per pair of blocks on
+// the Switch-Base-8 decode stack).  So the kernels of a step take turns: kernel number seq does
+// its planning at once but starts copying only when turn[0] (the number of migrations of this
+// step that have finished) has reached seq.  This orders link traffic only, no data depends on
+// it: the wait is bounded by the clock (half a second) and a kernel that gives up just copies
+// alongside its predecessor as before.  The turn passes on as soon as the FIRST workgroup of a
+// kernel is done (all have the same amount to copy, so the others are within their last loads:
+// the successor's first loads fill the link while those drain); only the step's last kernel
+// counts its workgroups (turn[1]) and its last one sets the turn back to 0, so that a captured
+// step replays with the same arguments.
+constexpr unsigned long long TURN_TIMEOUT_TICKS = 50000000ull;  // of the 100 MHz wall clock
+
+__device__ inline void wait_for_turn(uint32_t *turn, int seq) {
+    if (seq <= 0) return;  // uniform over the kernel
+    if (threadIdx.x == 0) {
+        const unsigned long long t0 = wall_clock64();
+        while (__hip_atomic_load(turn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)seq &&
+               wall_clock64() - t0 < TURN_TIMEOUT_TICKS)
+            __builtin_amdgcn_s_sleep(32);
+    }
+    __syncthreads();
+}
+
+__device__ inline void end_of_turn(uint32_t *turn, int seq, int last) {
+    if (seq < 0) return;  // uniform over the kernel
+    __syncthreads();      // every load of this workgroup has returned (its value went into a store)
+    if (threadIdx.x == 0) {
+        if (!last) {
+            atomicMax(turn, (uint32_t)seq + 1u);
+        } else if (atomicAdd(turn + 1, 1u) == gridDim.x - 1) {
+            __hip_atomic_store(turn + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(turn, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
 template <typename V>
 __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_kernel(
     const int32_t *__restrict__ idx, int n, int E, const char *__restrict__ src_block, size_t expert_stride,
     char *__restrict__ gen_base, size_t expert_bytes, int slots, int all, int32_t *__restrict__ unique_out,
-    uint32_t *flags) {
+    uint32_t *flags, uint32_t *turn, int seq, int last) {
     __shared__ int present[PGMOE_MAX_EXPERTS];
     __shared__ int list[PGMOE_MAX_EXPERTS];
     __shared__ int s_u;
@@ -53,6 +93,7 @@ __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_kernel(
         if (U > slots) atomicOr(flags, kFlagNoSlot);
     }
     if (U > slots) U = slots;
+    wait_for_turn(turn, seq);
 
     // all selected blobs form one range of U * upe vector units, dealt out grid-stride
     const unsigned upe = (unsigned)(expert_bytes / sizeof(V));
@@ -78,6 +119,7 @@ __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_kernel(
         reinterpret_cast<V *>(gen_base + (size_t)sl * expert_bytes)[of] =
             reinterpret_cast<const V *>(src_block + (size_t)list[sl] * expert_stride)[of];
     }
+    end_of_turn(turn, seq, last);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -109,7 +151,7 @@ __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_cache_kernel(
     const int32_t *__restrict__ idx, int n, int E, const char *__restrict__ src_block, size_t expert_stride,
     char *__restrict__ gen_base, size_t expert_bytes, int slots, char *__restrict__ cache_base, int C, int policy,
     const int32_t *__restrict__ state_in, int32_t *__restrict__ state_out, unsigned long long *__restrict__ table,
-    int32_t *__restrict__ stats_out, uint32_t *flags) {
+    int32_t *__restrict__ stats_out, uint32_t *flags, uint32_t *turn, int seq, int last) {
     __shared__ int present[PGMOE_MAX_EXPERTS];               // 0 not selected, 1 selected
     __shared__ int cp_src[PGMOE_MAX_EXPERTS];                // copies: source expert
     __shared__ unsigned long long cp_dst[PGMOE_MAX_EXPERTS]; // copies: destination address
@@ -212,6 +254,7 @@ __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_cache_kernel(
     __syncthreads();
     if (blockIdx.x == 0)
         for (int e = tid; e < E; e += FETCH_THREADS) table[e] = tbl[e];
+    wait_for_turn(turn, seq);
 
     const unsigned upe = (unsigned)(expert_bytes / sizeof(V));
     const unsigned total = (unsigned)s_counts[0] * upe;
@@ -221,12 +264,15 @@ __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_cache_kernel(
         reinterpret_cast<V *>(cp_dst[j])[of] =
             __builtin_nontemporal_load(reinterpret_cast<const V *>(src_block + (size_t)cp_src[j] * expert_stride) + of);
     }
+    end_of_turn(turn, seq, last);
 }
 
 size_t cache_state_bytes(const pgmoe_config &c) { return (size_t)c.n_blocks * 2 * CACHE_STATE_INTS * sizeof(int32_t); }
 
-int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, int n, hipStream_t s) {
+int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, int n, hipStream_t s, int seq, bool last) {
     const int gen = block % ctx->n_gen;
+    uint32_t *turn = ctx->dev_flags + 4;  // two counters in the flag block's first 64 bytes
+    const int is_last = last ? 1 : 0;
     char *gen_base = ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes;
     const char *src = ctx->store_dev + (size_t)block * ctx->block_stride;
     if (ctx->cfg.cache_slots > 0 && !all) {
@@ -239,11 +285,11 @@ int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, i
         if (ctx->expert_bytes % 16 == 0)
             hipLaunchKernelGGL(fetch_pull_cache_kernel<u32x4>, dim3(FETCH_GRID), dim3(FETCH_THREADS), 0, s, idx, n,
                                ctx->cfg.n_experts, src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, cache_base,
-                               C, ctx->cfg.cache_policy, st_in, st_out, table, stats, ctx->dev_flags);
+                               C, ctx->cfg.cache_policy, st_in, st_out, table, stats, ctx->dev_flags, turn, seq, is_last);
         else
             hipLaunchKernelGGL(fetch_pull_cache_kernel<unsigned int>, dim3(FETCH_GRID), dim3(FETCH_THREADS), 0, s, idx, n,
                                ctx->cfg.n_experts, src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, cache_base,
-                               C, ctx->cfg.cache_policy, st_in, st_out, table, stats, ctx->dev_flags);
+                               C, ctx->cfg.cache_policy, st_in, st_out, table, stats, ctx->dev_flags, turn, seq, is_last);
         PG_HIP(ctx, hipGetLastError());
         ctx->cache_parity[block] = par ^ 1;
         return PGMOE_OK;
@@ -251,11 +297,11 @@ int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, i
     if (ctx->expert_bytes % 16 == 0)
         hipLaunchKernelGGL(fetch_pull_kernel<u32x4>, dim3(FETCH_GRID), dim3(FETCH_THREADS), 0, s, idx, n, ctx->cfg.n_experts,
                            src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, all ? 1 : 0, ctx->dev_unique + block,
-                           ctx->dev_flags);
+                           ctx->dev_flags, turn, seq, is_last);
     else
         hipLaunchKernelGGL(fetch_pull_kernel<unsigned int>, dim3(FETCH_GRID), dim3(FETCH_THREADS), 0, s, idx, n,
                            ctx->cfg.n_experts, src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, all ? 1 : 0,
-                           ctx->dev_unique + block, ctx->dev_flags);
+                           ctx->dev_unique + block, ctx->dev_flags, turn, seq, is_last);
     PG_HIP(ctx, hipGetLastError());
     return PGMOE_OK;
 }

@@ -50,10 +50,13 @@ struct pgmoe_ctx {
 
     // device resources
     char *slot_pool;       // [n_gen][slots][expert_bytes]
-    uint32_t *dev_flags;   // sticky condition bits
+    uint32_t *dev_flags;   // [0] sticky condition bits; [4], [5] turn counters of the migration kernels (fetch.hip)
     int32_t *dev_unique;   // [n_blocks] distinct experts found by the pull kernel (dev_flags + 64 bytes)
     int32_t *dev_src_row;  // [n_blocks][max_tokens * k] grouped row -> token, written by each block's routing
     bool *routed;          // [n_blocks] host: this step's gate kernel already grouped the block's tokens
+    // turn-taking of a stack step's migration kernels on the host link (see fetch.hip): position of
+    // the next one in the step (-1: not inside a step), and the position of the step's last one
+    int pull_seq = -1, pull_last = -1;
     const char *store_dev; // device-visible address of the pinned host store
     bool pull;             // fetch with the device-side pull kernel
     int32_t *idx_staging;  // pinned host [max_tokens * k]
@@ -146,7 +149,10 @@ inline int reduce_lanes(int P) { return P <= 2 ? 1 : (P <= 8 ? 4 : 16); }
 // arithmetic, in the same order, as ffn_reduce_kernel followed by launch_combine.
 int launch_combine_partials(pgmoe_ctx *ctx, const float *partial, int P, int n_rows, const int32_t *row_of,
                             const float *prob, int T, void *y, const void *x_res, void *x_next, hipStream_t s);
-int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, int n, hipStream_t s);
+// seq: position among the migration kernels of the running stack step (they take turns on the
+// host link in that order), -1 for a kernel that is not part of one; last: the step's last one
+int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, int n, hipStream_t s, int seq = -1,
+                      bool last = false);
 size_t cache_state_bytes(const pgmoe_config &c);
 int launch_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, const float *prob, int T,
                    void *y, const void *x_res, void *x_next, hipStream_t s);
