@@ -318,7 +318,8 @@ int pgmoe_ffn_timing_end(pgmoe_ctx *ctx, int *n_out, float *total_ms_out, float 
  * after the point where the FFN waits for its experts, and at the end of the block.  The event
  * records cost several microseconds each, so tracing is for instrumented passes only.
  * pgmoe_get_block_trace() waits for the block's events of the LAST step and fills:
- *   fetch_ms   duration of the block's migration (copy stream);
+ *   fetch_ms   duration of the block's migration kernel (copy stream), which includes the time it
+ *              waits for its turn on the host link behind the migration before it;
  *   stall_ms   time the compute stream spent waiting for it (0 if the experts were there);
  *   compute_ms duration of the block on the compute stream (pre-gate, grouping, FFN, combine)
  *              minus stall_ms;
