@@ -27,17 +27,20 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 // which delays the EARLIER one: its block starts later, the pre-gate behind that block issues
 // the fetch after next later, and the link idles there instead (17-23 us per pair of blocks on
 // the Switch-Base-8 decode stack).  So the kernels of a step take turns: kernel number seq does
-// its planning at once but starts copying only when turn[0] (the number of migrations of this
-// step that have finished) has reached seq.  This orders link traffic only, no data depends on
+// its planning at once but starts copying only when turn[0] (how many of this step's migrations
+// have passed the turn on) has reached seq.  This orders link traffic only, no data depends on
 // it: the wait is bounded by the clock (half a second) and a kernel that gives up just copies
 // alongside its predecessor as before.  The turn passes on as soon as the FIRST workgroup of a
 // kernel is done (all have the same amount to copy, so the others are within their last loads:
 // the successor's first loads fill the link while those drain); only the step's last kernel
 // counts its workgroups (turn[1]) and its last one sets the turn back to 0, so that a captured
-// step replays with the same arguments.
+// step replays with the same arguments; the step's first kernel clears it as well, which limits
+// what a late straggler of the previous step (or a step that ended early) can leave behind to one
+// pair of kernels copying side by side.
 constexpr unsigned long long TURN_TIMEOUT_TICKS = 50000000ull;  // of the 100 MHz wall clock
 
 __device__ inline void wait_for_turn(uint32_t *turn, int seq) {
+    if (seq == 0 && blockIdx.x == 0 && threadIdx.x == 0) __hip_atomic_store(turn, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (seq <= 0) return;  // uniform over the kernel
     if (threadIdx.x == 0) {
         const unsigned long long t0 = wall_clock64();
