@@ -456,6 +456,29 @@ def test_switch_shaped_stacks(hx, name, blocks, steps, sample, fetch):
     stack.close()
 
 
+def test_migrations_of_a_step_take_turns_on_the_host_link(hx):
+    """Switch-Base-8 decode shape (one 9.4 MB expert per block): the migration kernels of a step
+    finish one after the other, a whole copy apart, instead of sharing the link in pairs (the
+    first of a pair then ends late and its neighbour right behind it).  Loose bound: a copy
+    takes about 165 us at link speed; consecutive fetches must end more than 100 us apart."""
+    H, B = hx
+    w = W.CONFIGS["cfg2"]
+    stack, gates, cache = make_stack(H, w)
+    stack.ctx.trace(True)
+    worst = []
+    for s in range(4):
+        stack.set_input(W.step_input(w, s))
+        stack.step()
+        torch.cuda.synchronize()
+        ends = [stack.ctx.block_trace(b).fetch_end_ms for b in range(w.n_blocks)]
+        gaps = np.diff(ends) * 1e3
+        say(f"  step {s}: fetches end {np.round(np.array(ends) * 1e3).astype(int).tolist()} us after the step's start")
+        worst.append(float(gaps.min()))
+    stack.ctx.trace(False)
+    assert min(worst[1:]) > 100.0, worst     # the first step also pays first-touch costs
+    stack.close()
+
+
 @pytest.mark.parametrize("distance,fetch,T,E,k", [(2, "pull", 16, 16, 1), (3, "pull", 5, 8, 2), (2, "memcpy", 16, 16, 1),
                                                    (3, "memcpy", 33, 12, 1)])
 def test_pregate_distance_routes_from_the_earlier_state_and_keeps_more_generations(hx, distance, fetch, T, E, k):
