@@ -197,6 +197,7 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
         if (rc == PGMOE_OK) H(hipMalloc((void **)&c->dev_src_row, (size_t)cfg->n_blocks * n_idx * sizeof(int32_t)), "hipMalloc(src_row)");
         if (rc == PGMOE_OK) H(hipHostMalloc((void **)&c->idx_staging, n_idx * sizeof(int32_t), hipHostMallocDefault), "hipHostMalloc(idx staging)");
         if (rc == PGMOE_OK) H(hipEventCreateWithFlags(&c->idx_ready, hipEventDisableTiming | hipEventReleaseToDevice), "hipEventCreate");
+        if (rc == PGMOE_OK) H(hipEventCreateWithFlags(&c->step_start, hipEventDisableTiming | hipEventReleaseToDevice), "hipEventCreate");
         if (rc == PGMOE_OK) H(hipStreamCreateWithFlags(&c->copy2, hipStreamNonBlocking), "hipStreamCreate");
         for (int g = 0; g < kGen && rc == PGMOE_OK; ++g) {
             // these two only order device work against device work: no host-visible release needed
@@ -236,6 +237,7 @@ int pgmoe_destroy(pgmoe_ctx *c) {
         if (c->dev_src_row) (void)hipFree(c->dev_src_row);
         if (c->idx_staging) (void)hipHostFree(c->idx_staging);
         if (c->idx_ready) (void)hipEventDestroy(c->idx_ready);
+        if (c->step_start) (void)hipEventDestroy(c->step_start);
         if (c->copy2) (void)hipStreamDestroy(c->copy2);
         for (int g = 0; g < kGen; ++g) {
             if (c->fetch_done[g]) (void)hipEventDestroy(c->fetch_done[g]);

@@ -144,14 +144,14 @@ static int fetch_impl(pgmoe_ctx *ctx, const char *fn, int block, bool all, const
     if (ctx->pull) {
         // device-side migration: the copy stream waits for the indices and for the generation
         // to be free, then one kernel dedupes and pulls; the host is not involved
-        if (!inline_fetch) {
+        if (!inline_fetch && !ctx->routed_on_copy_stream) {
             PG_HIP(ctx, hipEventRecord(ctx->idx_ready, cs));
             PG_HIP(ctx, hipStreamWaitEvent(ps, ctx->idx_ready, 0));
         }
         rc = wait_for_last_reader(ctx, gen, cs, ps);
         if (rc) return rc;
         if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_begin[block], ps));
-        const int seq = (ctx->pull_seq >= 0 && !inline_fetch) ? ctx->pull_seq++ : -1;
+        const int seq = ctx->pull_seq >= 0 ? ctx->pull_seq++ : -1;  // inside a step: its place in the queue for the link
         rc = launch_fetch_pull(ctx, block, all, topk_idx, n, ps, seq, seq >= 0 && seq == ctx->pull_last);
         if (rc) return rc;
         if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_end[block], ps));
@@ -417,15 +417,23 @@ static int launch_standin(pgmoe_ctx *ctx, void *stream) {
 // The gate that routes block g, evaluated on hidden state x, inside pgmoe_stack_step.  For a
 // decode-sized bf16 batch the gate kernel also groups block g's tokens by expert (offsets, row_of,
 // inverse map) and routed[g] says so; pgmoe_stack_step has validated the buffers.
-static int gate_for_block(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int g, const void *x, int T, void *stream) {
+// finish_routing (bf16 contexts): the call must leave the block fully grouped on `stream`, so the
+// grouping kernel follows the gate there when the gate kernel did not do it itself.
+static int gate_for_block(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int g, const void *x, int T, void *stream,
+                          bool finish_routing = false) {
     const pgmoe_config &c = ctx->cfg;
     const size_t nk = (size_t)T * c.top_k;
     const float *bias = io->gate_b ? io->gate_b[g] : nullptr;
     if (!aligned(x, 16) || !aligned(io->gate_w[g], 16) || !aligned(bias, 4))
         return fail(ctx, PGMOE_EINVAL, "pgmoe_stack_step: misaligned hidden state, gate weight or bias of block %d", g);
-    return launch_gate(ctx, x, io->gate_w[g], bias, T, io->topk_idx + (size_t)g * nk, io->topk_prob + (size_t)g * nk, nullptr,
-                       (hipStream_t)stream, io->row_of + (size_t)g * nk, io->expert_offsets + (size_t)g * (c.n_experts + 1),
-                       ctx->dev_src_row + (size_t)g * c.max_tokens * c.top_k, &ctx->routed[g]);
+    int32_t *row_of = io->row_of + (size_t)g * nk, *offs = io->expert_offsets + (size_t)g * (c.n_experts + 1);
+    int32_t *src_row = ctx->dev_src_row + (size_t)g * c.max_tokens * c.top_k;
+    int rc = launch_gate(ctx, x, io->gate_w[g], bias, T, io->topk_idx + (size_t)g * nk, io->topk_prob + (size_t)g * nk, nullptr,
+                         (hipStream_t)stream, row_of, offs, src_row, &ctx->routed[g]);
+    if (rc || !finish_routing || c.dtype != PGMOE_BF16 || ctx->routed[g]) return rc;
+    rc = launch_route(ctx, io->topk_idx + (size_t)g * nk, T, row_of, offs, src_row, (hipStream_t)stream);
+    if (rc == PGMOE_OK) ctx->routed[g] = true;
+    return rc;
 }
 
 // Token grouping and expert FFN of one block inside pgmoe_stack_step.  bf16: only the integer
@@ -539,11 +547,36 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     // queued back to back on the copy stream: the link never idles between them.
     const int N = ctx->distance;
     const int head = std::min(N, L - 1);
-    for (int g = 0; g <= head; ++g) {
-        rc = gate_for_block(ctx, io, g, x_at(0), T, compute_stream);
+    if (ctx->pull_seq >= 0 && N == 1 && c.dtype == PGMOE_BF16) {
+        // Block 0's fetch is exposed whatever is done, so it runs on the compute stream itself,
+        // right behind its gate: no stream hand-over (11-13 us) before the link starts working,
+        // and none before block 0's experts either.  Block 1's pre-gate and fetch go to the
+        // context's own copy stream together (stream order between them); that stream only has to
+        // be behind the start of this step, where x_0 is in place and block 1's buffers are free.
+        hipStream_t cs = (hipStream_t)compute_stream;
+        if (L > 1) {
+            PG_HIP(ctx, hipEventRecord(ctx->step_start, cs));
+            PG_HIP(ctx, hipStreamWaitEvent(ctx->copy2, ctx->step_start, 0));
+        }
+        rc = gate_for_block(ctx, io, 0, x_at(0), T, compute_stream);
         if (rc) return rc;
-        rc = pgmoe_fetch_experts(ctx, g, idx_at(g), T, compute_stream, copy_stream, nullptr);
+        rc = pgmoe_fetch_experts(ctx, 0, idx_at(0), T, compute_stream, compute_stream, nullptr);  // takes turn 0
         if (rc) return rc;
+        if (L > 1) {
+            rc = gate_for_block(ctx, io, 1, x_at(0), T, ctx->copy2, /*finish_routing=*/true);
+            if (rc) return rc;
+            ctx->routed_on_copy_stream = true;  // turn 1 is odd: the fetch goes to the same stream
+            rc = pgmoe_fetch_experts(ctx, 1, idx_at(1), T, compute_stream, copy_stream, nullptr);
+            ctx->routed_on_copy_stream = false;
+            if (rc) return rc;
+        }
+    } else {
+        for (int g = 0; g <= head; ++g) {
+            rc = gate_for_block(ctx, io, g, x_at(0), T, compute_stream);
+            if (rc) return rc;
+            rc = pgmoe_fetch_experts(ctx, g, idx_at(g), T, compute_stream, copy_stream, nullptr);
+            if (rc) return rc;
+        }
     }
 
     for (int i = 0; i < L; ++i) {

@@ -57,6 +57,10 @@ struct pgmoe_ctx {
     // turn-taking of a stack step's migration kernels on the host link (see fetch.hip): position of
     // the next one in the step (-1: not inside a step), and the position of the step's last one
     int pull_seq = -1, pull_last = -1;
+    // set by pgmoe_stack_step around one fetch: the routing was computed on the copy stream the
+    // fetch will use (stream order covers it), so no event from the compute stream is needed
+    bool routed_on_copy_stream = false;
+    hipEvent_t step_start = nullptr;  // compute stream -> the context's own copy stream at the start of a step
     const char *store_dev; // device-visible address of the pinned host store
     bool pull;             // fetch with the device-side pull kernel
     int32_t *idx_staging;  // pinned host [max_tokens * k]
