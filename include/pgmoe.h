@@ -322,7 +322,8 @@ int pgmoe_ffn_timing_end(pgmoe_ctx *ctx, int *n_out, float *total_ms_out, float 
  * pgmoe_get_block_trace() waits for the block's events of the LAST step and fills:
  *   fetch_ms   duration of the block's migration kernel (copy stream), which includes the time it
  *              waits for its turn on the host link behind the migration before it;
- *   stall_ms   time the compute stream spent waiting for it (0 if the experts were there);
+ *   stall_ms   time the compute stream spent waiting for it (0 if the experts were there; all of
+ *              fetch_ms and more when the migration ran on the compute stream itself);
  *   compute_ms duration of the block on the compute stream (pre-gate, grouping, FFN, combine)
  *              minus stall_ms;
  *   fetch_start_ms, fetch_end_ms, block_start_ms, block_end_ms: the same events as offsets

@@ -162,6 +162,7 @@ static int fetch_impl(pgmoe_ctx *ctx, const char *fn, int block, bool all, const
         ctx->fetched_block[gen] = block;
         ctx->live_slots[gen] = -1;  // known on the device only
         st.timed = ctx->fetch_timing;
+        st.in_line = inline_fetch;
         st.pulled = true;
         st.cached = ctx->gen_table[gen];
         st.s.n_unique = -1;
@@ -339,6 +340,8 @@ int pgmoe_get_block_trace(pgmoe_ctx *ctx, int block, pgmoe_block_trace *out) {
     PG_HIP(ctx, el(ctx->ev_c0[0], ctx->ev_c0[block], &out->block_start_ms));
     PG_HIP(ctx, el(ctx->ev_c0[0], ctx->ev_c1[block], &out->block_end_ms));
     out->stall_ms = stall > 0.f ? stall : 0.f;
+    // a fetch on the compute stream itself is waited for in stream order, not at the event wait
+    if (ctx->stats[block].in_line) out->stall_ms += out->fetch_ms;
     out->compute_ms = total - out->stall_ms;
     return PGMOE_OK;
 }

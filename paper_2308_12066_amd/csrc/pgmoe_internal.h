@@ -29,6 +29,7 @@ struct BlockStats {
     bool timed;   // fetch_begin/fetch_end were recorded for this block
     bool pulled;  // fetched by the pull kernel: counts live on the device
     bool cached;  // ... through the expert cache: counts in cache_stats
+    bool in_line; // the fetch ran on the compute stream itself: the stream stood still for all of it
 };
 
 }  // namespace pgmoe
