@@ -23,6 +23,11 @@ int hip_fail(pgmoe_ctx *ctx, hipError_t e, const char *what) {
     return fail(ctx, PGMOE_EHIP, "%s failed: %s", what, hipGetErrorString(e));
 }
 
+static int default_slots(const pgmoe_config &c) {
+    int64_t n = (int64_t)c.max_tokens * c.top_k;
+    return (int)std::min<int64_t>(c.n_experts, n);
+}
+
 int check_config(const pgmoe_config *c, char *buf, size_t n) {
 #define BAD(...)                    \
     do {                            \
@@ -53,13 +58,17 @@ int check_config(const pgmoe_config *c, char *buf, size_t n) {
         BAD("pregate_distance=%d outside 0..%d", c->pregate_distance, PGMOE_MAX_PREGATE_DISTANCE);
     if (c->cache_slots > 0 && (c->flags & PGMOE_FLAG_FETCH_MEMCPY))
         BAD("the expert cache is kept by the device-side pull engine: not available with PGMOE_FLAG_FETCH_MEMCPY");
+    if (!(c->flags & PGMOE_FLAG_FETCH_MEMCPY)) {
+        // the pull kernels number the 16-byte (4-byte if the blob is no multiple of 16) units of
+        // everything one migration may copy with 32 bits
+        const uint64_t eb = (uint64_t)2 * c->d_model * c->d_ff * (c->dtype == PGMOE_F32 ? 4 : 2);
+        const uint64_t slots = c->slots_per_gen > 0 ? c->slots_per_gen : default_slots(*c);
+        if ((slots + c->cache_slots) * (eb / (eb % 16 ? 4 : 16)) >= (1ull << 32) - (1ull << 20))
+            BAD("%llu slots of %llu-byte experts are more than one device-side migration can address: fewer slots_per_gen, "
+                "or PGMOE_FLAG_FETCH_MEMCPY", (unsigned long long)(slots + c->cache_slots), (unsigned long long)eb);
+    }
     return PGMOE_OK;
 #undef BAD
-}
-
-static int default_slots(const pgmoe_config &c) {
-    int64_t n = (int64_t)c.max_tokens * c.top_k;
-    return (int)std::min<int64_t>(c.n_experts, n);
 }
 
 }  // namespace pgmoe

@@ -555,7 +555,8 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
         // right behind its gate: no stream hand-over (11-13 us) before the link starts working,
         // and none before block 0's experts either.  Block 1's pre-gate and fetch go to the
         // context's own copy stream together (stream order between them); that stream only has to
-        // be behind the start of this step, where x_0 is in place and block 1's buffers are free.
+        // be behind the start of this step, where x_0 is in place, block 1's buffers are free and
+        // the last reader of block 1's slot generation (an FFN of the previous step) is queued.
         hipStream_t cs = (hipStream_t)compute_stream;
         if (L > 1) {
             PG_HIP(ctx, hipEventRecord(ctx->step_start, cs));

@@ -45,6 +45,17 @@ def test_create_rejects_bad_config(bad):
     assert B.expert_bytes(cfg(**bad)) == 0
 
 
+def test_create_rejects_more_than_the_pull_kernels_can_address():
+    """The device-side migration numbers 16-byte units with 32 bits: a slot set of 64 GiB or more
+    is refused at creation unless the copy-engine path is chosen."""
+    big = dict(d_model=32768, d_ff=65536, dtype=B.F32, n_experts=8, top_k=1, max_tokens=8)     # 16 GiB per expert
+    with pytest.raises(B.PgmoeError) as ei:
+        B.Context(cfg(**big))
+    assert ei.value.code == B.EINVAL and "PGMOE_FLAG_FETCH_MEMCPY" in str(ei.value)
+    B.Context(cfg(**big, slots_per_gen=3)).close()
+    B.Context(cfg(**dict(big, flags=B.FLAG_HOST_ONLY | B.FLAG_FETCH_MEMCPY))).close()
+
+
 def test_expert_bytes():
     assert B.expert_bytes(cfg(d_model=768, d_ff=3072)) == 9437184
     assert B.expert_bytes(cfg(d_model=1024, d_ff=4096)) == 16777216

@@ -474,6 +474,9 @@ def test_migrations_of_a_step_take_turns_on_the_host_link(hx):
         gaps = np.diff(ends) * 1e3
         say(f"  step {s}: fetches end {np.round(np.array(ends) * 1e3).astype(int).tolist()} us after the step's start")
         worst.append(float(gaps.min()))
+        # block 0's experts are needed at once: nothing hides that migration, wherever it runs
+        t0 = stack.ctx.block_trace(0)
+        assert t0.stall_ms >= 0.9 * t0.fetch_ms > 0.1, (t0.stall_ms, t0.fetch_ms)
     stack.ctx.trace(False)
     assert min(worst[1:]) > 100.0, worst     # the first step also pays first-touch costs
     stack.close()
