@@ -66,7 +66,8 @@ typedef enum { PGMOE_F32 = 0, PGMOE_BF16 = 1 } pgmoe_dtype;
 #define PGMOE_MAX_EXPERTS 256 /* the paper's largest model has 256 experts per block */
 
 typedef struct {
-    int32_t d_model;       /* bf16: multiple of 64; f32: any >= 1 */
+    int32_t d_model;       /* bf16: 64, 128, 256, 512, 768, 1024 or 2048 (the sizes expert kernels are
+                              built for; pack/unpack take any multiple of 64); f32: any >= 1 */
     int32_t d_ff;          /* bf16: multiple of 64 */
     int32_t n_experts;     /* 1 .. PGMOE_MAX_EXPERTS */
     int32_t top_k;         /* 1 .. n_experts */
@@ -312,7 +313,9 @@ int pgmoe_ffn_timing_begin(pgmoe_ctx *ctx, int max_launches);
 /* Name of the main kernel pgmoe_expert_ffn() launches for n_rows permuted rows in this context
  * ("ffn_decode_kernel", "ffn_fused_kernel", "ffn_gemm_up_kernel+ffn_gemm_down_kernel" or
  * "ffn_f32_hidden_kernel+ffn_f32_out_kernel"): the
- * name to look for in a profiler's kernel trace.  Static string; NULL if ctx is NULL. */
+ * name to look for in a profiler's kernel trace.  Static string; NULL if ctx is NULL or no kernel
+ * is built for that launch (pgmoe_expert_ffn() would return PGMOE_EINVAL; no accepted
+ * configuration has such a launch). */
 const char *pgmoe_ffn_kernel_name(const pgmoe_ctx *ctx, int n_rows);
 int pgmoe_ffn_timing_end(pgmoe_ctx *ctx, int *n_out, float *total_ms_out, float *pair_overhead_ms_out);
 

@@ -258,8 +258,9 @@ class Context:
         self._check(lib.pgmoe_device_flags(self._h, byref(f)))
         return f.value
 
-    def ffn_kernel_name(self, n_rows: int) -> str:
-        return lib.pgmoe_ffn_kernel_name(self._h, n_rows).decode()
+    def ffn_kernel_name(self, n_rows: int):
+        name = lib.pgmoe_ffn_kernel_name(self._h, n_rows)
+        return name.decode() if name is not None else None
 
     def ffn_timing_begin(self, max_launches: int):
         self._check(lib.pgmoe_ffn_timing_begin(self._h, max_launches))

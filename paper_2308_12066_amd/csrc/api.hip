@@ -160,6 +160,9 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
     *out = nullptr;
     char buf[256];
     if (check_config(cfg, buf, sizeof buf) != PGMOE_OK) return fail(nullptr, PGMOE_EINVAL, "pgmoe_create: %s", buf);
+    if (cfg->dtype == PGMOE_BF16 && !ffn_supports_d_model(cfg->d_model))
+        return fail(nullptr, PGMOE_EINVAL, "pgmoe_create: no bf16 expert kernel is built for d_model=%d (built: 64, 128, 256, 512, 768, 1024, 2048)",
+                    cfg->d_model);
     pgmoe_ctx *c = new (std::nothrow) pgmoe_ctx();
     if (!c) return fail(nullptr, PGMOE_EINVAL, "pgmoe_create: out of host memory");
     c->cfg = *cfg;

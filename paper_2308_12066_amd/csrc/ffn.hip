@@ -401,7 +401,7 @@ FfnPlan plan_ffn(const pgmoe_config &c, int n_rows) {
     // the chip otherwise, 8 for the 64-row chunks (halves the accumulators per wavefront)
     int nw = 4;
     if (mt == 1 && active * (c.d_ff / 64) < 256 && (kt == 24 || kt == 32)) nw = 2;
-    if (mt == 4 && (kt == 24 || kt == 32)) nw = 8;
+    if (mt == 4 && (kt == 24 || kt == 32) && c.d_ff % 128 == 0) nw = 8;
     if (mt == 4 && nw == 4 && kt > 24) mt = 2;
     if (mt == 2 && kt > 32) mt = 1;
     p.mt = mt;
@@ -419,6 +419,27 @@ FfnPlan plan_ffn(const pgmoe_config &c, int n_rows) {
     return p;
 }
 
+// Instantiations of ffn_fused_kernel that are built: X(MT, KT, NW, D) = 16*MT rows per chunk,
+// d_model = 32*KT, NW wavefronts, prefetch ring of D tiles.  plan_ffn only ever picks from this
+// list for a d_model that appears in it (pgmoe_create refuses any other d_model for bf16).
+#define PG_FUSED_CASES(X)                                                                                   \
+    X(1, 2, 4, 4) X(1, 4, 4, 8) X(1, 8, 4, 16) X(1, 16, 4, 16) X(1, 24, 4, 16) X(1, 32, 4, 16) X(1, 64, 4, 16) \
+    X(1, 24, 2, 24) X(1, 32, 2, 24)                                                                         \
+    X(2, 2, 4, 4) X(2, 4, 4, 8) X(2, 8, 4, 16) X(2, 16, 4, 16) X(2, 24, 4, 16) X(2, 32, 4, 16)              \
+    X(4, 2, 4, 4) X(4, 4, 4, 8) X(4, 8, 4, 16) X(4, 16, 4, 16) X(4, 24, 4, 16) X(4, 24, 8, 8) X(4, 32, 8, 8)
+
+static bool fused_case_built(int mt, int kt, int nw) {
+#define X(MT_, KT_, NW_, D_) \
+    if (mt == MT_ && kt == KT_ && nw == NW_) return true;
+    PG_FUSED_CASES(X)
+#undef X
+    return false;
+}
+
+// Every d_model of the list has the 16-row, four-wavefront instantiation; what else plan_ffn may
+// pick for it is in the list too (checked shape by shape by the host-side tests).
+bool ffn_supports_d_model(int d_model) { return d_model % 32 == 0 && fused_case_built(1, d_model / 32, 4); }
+
 // The decode-sized kernel serves launches of 16-row chunks split into one partial per
 // 32-column sub-slab (what plan_ffn picks when only a few experts are active).
 static bool uses_decode_kernel(const pgmoe_config &c, const FfnPlan &p) {
@@ -429,7 +450,9 @@ static bool uses_decode_kernel(const pgmoe_config &c, const FfnPlan &p) {
 const char *ffn_kernel_name(const pgmoe_config &c, int n_rows) {
     if (c.dtype == PGMOE_F32) return "ffn_f32_hidden_kernel+ffn_f32_out_kernel";
     if (uses_gemm_kernels(c, n_rows)) return "ffn_gemm_up_kernel+ffn_gemm_down_kernel";
-    return uses_decode_kernel(c, plan_ffn(c, n_rows)) ? "ffn_decode_kernel" : "ffn_fused_kernel";
+    const FfnPlan p = plan_ffn(c, n_rows);
+    if (uses_decode_kernel(c, p)) return "ffn_decode_kernel";
+    return fused_case_built(p.mt, c.d_model / 32, p.nw) && c.d_ff % (16 * p.nw) == 0 ? "ffn_fused_kernel" : nullptr;
 }
 
 size_t ffn_workspace_bytes(const pgmoe_config &c) {
@@ -538,15 +561,12 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
         return launch_ffn_reduce(ctx, partial, p.n_partial, n_rows, y_perm, s);
     }
     if (c.d_ff % (16 * p.nw)) return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: d_ff=%d is not a multiple of the %d-column sub-slab", c.d_ff, 16 * p.nw);
-#define PG_CASE(MT_, KT_, NW_, D_) \
-    if (p.mt == MT_ && kt == KT_ && p.nw == NW_) return launch_fused<MT_, KT_, NW_, D_>(ctx, p, w_base, w_stride, slot_by_rank, n_slots, x_perm, offsets, n_rows, y_perm, workspace, s, keep_partials, table, src_row)
-    PG_CASE(1, 2, 4, 4); PG_CASE(1, 4, 4, 8); PG_CASE(1, 8, 4, 16); PG_CASE(1, 16, 4, 16); PG_CASE(1, 24, 4, 16);
-    PG_CASE(1, 32, 4, 16); PG_CASE(1, 64, 4, 16); PG_CASE(1, 24, 2, 24); PG_CASE(1, 32, 2, 24);
-    PG_CASE(2, 2, 4, 4); PG_CASE(2, 4, 4, 8); PG_CASE(2, 8, 4, 16); PG_CASE(2, 16, 4, 16); PG_CASE(2, 24, 4, 16);
-    PG_CASE(2, 32, 4, 16);
-    PG_CASE(4, 2, 4, 4); PG_CASE(4, 4, 4, 8); PG_CASE(4, 8, 4, 16); PG_CASE(4, 16, 4, 16); PG_CASE(4, 24, 4, 16);
-    PG_CASE(4, 24, 8, 8); PG_CASE(4, 32, 8, 8);
-#undef PG_CASE
+#define X(MT_, KT_, NW_, D_)                                                                                                  \
+    if (p.mt == MT_ && kt == KT_ && p.nw == NW_)                                                                              \
+        return launch_fused<MT_, KT_, NW_, D_>(ctx, p, w_base, w_stride, slot_by_rank, n_slots, x_perm, offsets, n_rows, y_perm, \
+                                               workspace, s, keep_partials, table, src_row);
+    PG_FUSED_CASES(X)
+#undef X
     return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: no bf16 kernel built for d_model=%d with %d-row chunks and %d wavefronts", c.d_model, 16 * p.mt, p.nw);
 }
 

@@ -128,7 +128,8 @@ struct FfnPlan {
 };
 FfnPlan plan_ffn(const pgmoe_config &cfg, int n_rows);
 size_t ffn_workspace_bytes(const pgmoe_config &cfg);
-const char *ffn_kernel_name(const pgmoe_config &cfg, int n_rows);
+const char *ffn_kernel_name(const pgmoe_config &cfg, int n_rows);  // nullptr: no kernel is built for this launch
+bool ffn_supports_d_model(int d_model);                          // bf16: expert kernels are built for this d_model
 
 // Kernel launchers (each validates nothing: callers did).  All asynchronous on `s`.
 // row_of / offsets / src_row / routed (all or none): if the launch can also group the tokens by

@@ -154,6 +154,28 @@ def test_nonmoe_standin_setter_validates_its_argument():
     c.close()
 
 
+def test_every_accepted_bf16_shape_has_an_expert_kernel():
+    """pgmoe_create accepts a bf16 d_model only if expert kernels are built for it, and for every
+    accepted shape and row count the launch plan names a kernel that exists."""
+    built = (64, 128, 256, 512, 768, 1024, 2048)
+    for d in range(64, 2049, 64):
+        if d in built:
+            continue
+        with pytest.raises(B.PgmoeError) as ei:
+            B.Context(cfg(d_model=d))
+        assert ei.value.code == B.EINVAL and "no bf16 expert kernel" in str(ei.value)
+    rows = (1, 2, 5, 16, 17, 40, 64, 100, 191, 192, 255, 700, 3000, 4096, 20000)
+    for d in built:
+        for f in (64, 192, 256, 320, 1024, 3072, 4096):
+            for E in (1, 3, 8, 64, 256):
+                ctx = B.Context(cfg(d_model=d, d_ff=f, n_experts=E, top_k=1, max_tokens=20000))
+                try:
+                    for n in rows:
+                        assert ctx.ffn_kernel_name(n) is not None, (d, f, E, n)
+                finally:
+                    ctx.close()
+
+
 def test_pack_f32_is_plain_concatenation():
     c = cfg(d_model=6, d_ff=10, dtype=B.F32)
     g = np.random.default_rng(0)

@@ -48,7 +48,7 @@ def small_workload(dtype, T, d, f, E, k, L=2, zipf=0.0, offloaded=False, index=4
 GATE_CASES = [
     ("f32", 32, 64, 8, 1), ("f32", 37, 100, 5, 2), ("f32", 9, 1500, 12, 3), ("bf16", 1, 768, 8, 1),
     ("bf16", 16, 768, 64, 1), ("bf16", 64, 1024, 128, 2), ("bf16", 333, 768, 128, 1), ("bf16", 7, 256, 256, 4),
-    ("bf16", 8, 64, 100, 100), ("f32", 5, 64, 1, 1),
+    ("bf16", 8, 64, 100, 100), ("f32", 5, 64, 1, 1), ("bf16", 20, 2048, 16, 2),
 ]
 
 
@@ -231,6 +231,10 @@ FFN_CASES = [
     ("bf16", 256, 512, 3, [0, 700, 5]),
     ("bf16", 512, 1024, 4, [600, 700, 500, 760]),              # enough row chunks for two K slices instead of four
     ("bf16", 1024, 4096, 2, [333, 290]),                       # the two GEMMs on the Switch-Large expert shape
+    # the largest d_model the bf16 path takes (16-row chunks only there), fused kernel and the two GEMMs
+    ("bf16", 2048, 256, 3, [5, 0, 40]),
+    ("bf16", 2048, 256, 2, [200, 260]),
+    ("bf16", 768, 192, 2, [30, 50]),                           # 64-row chunks with a d_ff that has no 128-column sub-slabs
 ]
 
 
