@@ -415,6 +415,10 @@ FfnPlan plan_ffn(const pgmoe_config &c, int n_rows) {
     const double traffic_cap = 0.06 * (double)active * c.d_ff / (2.0 * n_rows);
     want = std::max(1, std::min(want, (int)traffic_cap));
     p.n_partial = smallest_divisor_at_least(nsub, std::min(want, nsub));
+    if (n_rows > 4096 && p.n_partial > 16) {  // what ffn_workspace_bytes sets aside for launches this large
+        p.n_partial = 16;
+        while (nsub % p.n_partial) --p.n_partial;
+    }
     p.f_range = c.d_ff / p.n_partial;
     return p;
 }

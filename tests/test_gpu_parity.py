@@ -234,6 +234,7 @@ FFN_CASES = [
     # the largest d_model the bf16 path takes (16-row chunks only there), fused kernel and the two GEMMs
     ("bf16", 2048, 256, 3, [5, 0, 40]),
     ("bf16", 2048, 256, 2, [200, 260]),
+    ("bf16", 1024, 4096, 3, [40, 25, 33]),                     # 64-row chunks at d_model 1024: the largest LDS footprint
     ("bf16", 768, 192, 2, [30, 50]),                           # 64-row chunks with a d_ff that has no 128-column sub-slabs
 ]
 
