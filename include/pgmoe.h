@@ -294,6 +294,8 @@ typedef struct {
     void *y_perm;               /* dev [T*k, d] scratch */
     void *workspace;            /* dev, pgmoe_workspace_bytes() */
 } pgmoe_step_buffers;
+/* T in the shapes above is the T of the call (0 <= T <= max_tokens): the arrays are packed for it,
+ * whatever max_tokens the context was created with. */
 int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *compute_stream,
                      void *copy_stream);
 

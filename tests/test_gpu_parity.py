@@ -738,6 +738,38 @@ def test_stack_step_equals_the_primitive_call_sequence(hx, dtype, T, d, f, E, k,
     stack.close()
 
 
+def test_a_step_with_fewer_tokens_than_max_tokens_packs_its_arrays_for_that_T(hx):
+    """pgmoe_stack_step lays every per-step array out for the T of the call.  A context created for
+    64 tokens, stepped with 5, must give exactly what a context created for 5 tokens gives."""
+    H, B = hx
+    T, L, d, k, E = 5, 3, 128, 2, 8
+    w = small_workload("bf16", T, d, 256, E, k, L=L, offloaded=True, index=61)
+    tight, gates, cache = make_stack(H, w, threads=4, weight_scale=4.0)
+    tight.set_input(W.step_input(w, 0))
+    tight.step()
+    st = check_stack_step(H, w, tight, gates, cache, label="tight")
+    say(f"  tight context: {st}")
+    roomy = H.Stack(w, tight.store, gates=gates, max_tokens=64)
+
+    def packed(t, *shape):      # the first prod(shape) elements of a buffer allocated for 64 tokens
+        n = int(np.prod(shape))
+        return t.reshape(-1)[:n].view(*shape)
+
+    packed(roomy.x_states, L + 1, T, d)[0].copy_(tight.x_states[0])
+    torch.cuda.synchronize()
+    roomy.step(T=T)
+    torch.cuda.synchronize()
+    assert torch.equal(packed(roomy.x_states, L + 1, T, d), tight.x_states)
+    assert torch.equal(packed(roomy.y_blocks, L, T, d), tight.y_blocks)
+    assert torch.equal(packed(roomy.topk_idx, L, T, k), tight.topk_idx)
+    assert torch.equal(packed(roomy.topk_prob, L, T, k), tight.topk_prob)
+    assert torch.equal(packed(roomy.row_of, L, T * k), tight.row_of)
+    assert torch.equal(roomy.expert_offsets, tight.expert_offsets)
+    assert roomy.ctx.device_flags() == 0
+    roomy.close()
+    tight.close()
+
+
 STACK_SHAPES = [
     # dtype, T, d, f, E, k, L, offloaded, fetch, pre-gate distance
     ("bf16", 1, 64, 64, 8, 1, 1, True, "pull", 0),        # one block: the step's first migration is also its last
