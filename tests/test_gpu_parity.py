@@ -171,6 +171,35 @@ def test_permute_empty_and_bad_index(hx):
     ctx.close()
 
 
+@pytest.mark.parametrize("fetch", ["pull", "memcpy"])
+def test_every_call_takes_an_empty_batch(hx, fetch):
+    """T = 0 (n_rows = 0) is a valid no-op everywhere: nothing is written, nothing is migrated."""
+    H, B = hx
+    w = small_workload("bf16", 8, 64, 64, 4, 2, L=2, offloaded=True, index=62)
+    stack, gates, cache = make_stack(H, w, threads=2, flags=B.FLAG_FETCH_MEMCPY if fetch == "memcpy" else 0)
+    ctx, T, k, d = stack.ctx, w.tokens, w.top_k, w.d_model
+    x = H.to_device(W.step_input(w, 0), "bf16")
+    idx = torch.full((T, k), -7, dtype=torch.int32, device="cuda")
+    prob = torch.full((T, k), -7.0, dtype=torch.float32, device="cuda")
+    row_of = torch.full((T * k,), -7, dtype=torch.int32, device="cuda")
+    offs = torch.full((w.n_experts + 1,), -7, dtype=torch.int32, device="cuda")
+    y = torch.full((T * k, d), 7.0, dtype=torch.bfloat16, device="cuda")
+    ctx.pregate_topk(x, stack.gate_w[0], stack.gate_b[0], 0, idx, prob, None, stack.compute)
+    assert ctx.fetch_experts(0, idx, 0, stack.compute, stack.copy) == 0
+    ctx.expert_ffn(0, x, offs, 0, y, stack.workspace, stack.compute)
+    ctx.combine(y, row_of, prob, 0, y, None, None, stack.compute)
+    torch.cuda.synchronize()
+    assert (idx == -7).all() and (prob == -7).all() and (y == 7).all() and (row_of == -7).all()
+    fs = ctx.fetch_stats(0)
+    assert fs.n_unique == 0 and fs.bytes_copied == 0
+    before = stack.x_states.clone()
+    stack.step(T=0)
+    torch.cuda.synchronize()
+    assert torch.equal(stack.x_states, before)
+    assert ctx.device_flags() == 0
+    stack.close()
+
+
 # ------------------------------------------------------------------------------ expert FFN
 def run_ffn_case(H, B, dtype, d, f, E, counts, seed, scale=0.05):
     """Resident store of E experts; counts[e] rows for expert e.  Returns (gpu y_perm, oracle y_perm)."""
