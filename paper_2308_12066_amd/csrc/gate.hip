@@ -24,37 +24,67 @@ constexpr int GATE_THREADS = 256;
 __device__ inline float to_float(float v) { return v; }
 __device__ inline float to_float(__bf16 v) { return (float)v; }
 
-// (value, index) arg-max over a group of 16 lanes; equal values keep the lower index.
-__device__ inline void group_argmax(float &v, int &i) {
-#pragma unroll
-    for (int off = 8; off >= 1; off >>= 1) {
-        const float ov = __shfl_xor(v, off, 16);
-        const int oi = __shfl_xor(i, off, 16);
-        if (ov > v || (ov == v && oi < i)) {
-            v = ov;
-            i = oi;
-        }
+// Reductions over a group of 16 lanes (one DPP row) by rotating the row by 8, 4, 2 and 1 lanes:
+// every lane ends with the reduction over all 16, each step is one VALU operation (no LDS
+// crossbar traffic as with a shuffle).  All 64 lanes of the wavefront must be active.
+template <int N>
+__device__ inline int row_ror(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, 0x120 + N, 0xf, 0xf, false);  // row_ror:N
+}
+template <int N>
+__device__ inline float row_ror(float v) {
+    return __int_as_float(row_ror<N>(__float_as_int(v)));
+}
+__device__ inline float group_max(float m) {
+    m = fmaxf(m, row_ror<8>(m));
+    m = fmaxf(m, row_ror<4>(m));
+    m = fmaxf(m, row_ror<2>(m));
+    return fmaxf(m, row_ror<1>(m));
+}
+__device__ inline float group_sum(float s) {  // fixed order: bit-reproducible
+    s += row_ror<8>(s);
+    s += row_ror<4>(s);
+    s += row_ror<2>(s);
+    return s + row_ror<1>(s);
+}
+template <int N>
+__device__ inline void argmax_step(float &v, int &i) {
+    const float ov = row_ror<N>(v);
+    const int oi = row_ror<N>(i);
+    if (ov > v || (ov == v && oi < i)) {
+        v = ov;
+        i = oi;
     }
+}
+// (value, index) arg-max over the group; equal values keep the lower index.
+__device__ inline void group_argmax(float &v, int &i) {
+    argmax_step<8>(v, i);
+    argmax_step<4>(v, i);
+    argmax_step<2>(v, i);
+    argmax_step<1>(v, i);
 }
 
 // Softmax over the E logits of each token and k rounds of arg-max (ties to the lowest index,
 // NaN ranks as -infinity and raises the NaN flag).  zs: LDS [tokens][zstride] logits.
 // Sixteen lanes per token, so a wavefront works on four tokens at once; lane s of a group holds
-// experts s, s+16, s+32, ... (at most 16 of them, E <= 256).
-__device__ inline void softmax_topk(const float *zs, int zstride, int t0, int nt, int E, int k,
-                                    int32_t *__restrict__ idx_out, float *__restrict__ prob_out,
-                                    float *__restrict__ probs_out, uint32_t *flags,
-                                    int32_t *idx_lds = nullptr) {  // nullable: LDS copy [nt*k] of the chosen indices
+// experts s, s+16, s+32, ...: NQ of them (compile time, E <= 16*NQ), fully unrolled without a
+// branch per slice (a skipped slice of a 16-slice version still costs its branch, some 60 clocks,
+// which is what a batch-1 gate with 8 experts then spends its time on).
+template <int NQ>
+__device__ inline void softmax_topk_n(const float *zs, int zstride, int t0, int nt, int E, int k,
+                                      int32_t *__restrict__ idx_out, float *__restrict__ prob_out,
+                                      float *__restrict__ probs_out, uint32_t *flags, int32_t *idx_lds) {
     const int tid = threadIdx.x;
     const int sub = tid & 15, grp = tid >> 4;  // 16 lanes per group
     bool any_nan = false;
-    for (int tb = 0; tb < nt; tb += (int)blockDim.x / 16) {  // uniform trip count; idle groups just skip the writes
+    for (int tb = 0; tb < nt; tb += (int)blockDim.x / 16) {
+        if (tb + (grp & ~3) >= nt) continue;  // none of this wavefront's four tokens exists (uniform over the wavefront)
         const int t = tb + grp;
-        const bool live = t < nt;
-        float v[16];
+        const bool live = t < nt;  // idle groups of a live wavefront just skip the writes
+        float v[NQ];
         float m = -INFINITY;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
+        for (int q = 0; q < NQ; ++q) {
             const int ee = sub + 16 * q;
             float z = (live && ee < E) ? zs[t * zstride + ee] : -INFINITY;
             if (z != z) {
@@ -64,21 +94,19 @@ __device__ inline void softmax_topk(const float *zs, int zstride, int t0, int nt
             v[q] = z;
             m = fmaxf(m, z);
         }
+        m = group_max(m);
+        float p[NQ], s = 0.f;
 #pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 16));
-        float p[16], s = 0.f;
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
+        for (int q = 0; q < NQ; ++q) {
             p[q] = (sub + 16 * q < E) ? expf(v[q] - m) : 0.f;
             s += p[q];
         }
-#pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) s += __shfl_xor(s, off, 16);
+        s = group_sum(s);
         const float inv = 1.f / s;
         const size_t tok = (size_t)(t0 + t);
         if (probs_out && live) {
 #pragma unroll
-            for (int q = 0; q < 16; ++q)
+            for (int q = 0; q < NQ; ++q)
                 if (sub + 16 * q < E) probs_out[tok * E + sub + 16 * q] = p[q] * inv;
         }
         unsigned taken = 0;
@@ -86,7 +114,7 @@ __device__ inline void softmax_topk(const float *zs, int zstride, int t0, int nt
             float bv = -INFINITY;
             int bi = 0x7fffffff;
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
+            for (int q = 0; q < NQ; ++q) {
                 const int ee = sub + 16 * q;
                 // strict > keeps the lowest index of this lane; untaken -inf entries still compete by index
                 if (ee < E && !(taken >> q & 1) && (bi == 0x7fffffff || v[q] > bv)) {
@@ -95,9 +123,7 @@ __device__ inline void softmax_topk(const float *zs, int zstride, int t0, int nt
                 }
             }
             group_argmax(bv, bi);
-#pragma unroll
-            for (int q = 0; q < 16; ++q)
-                if (sub + 16 * q == bi) taken |= 1u << q;
+            if ((bi & 15) == sub) taken |= 1u << (bi >> 4);  // the lane that holds the winner retires it
             if (sub == 0 && live) {
                 idx_out[tok * k + j] = bi;
                 prob_out[tok * k + j] = expf(bv - m) * inv;
@@ -106,6 +132,21 @@ __device__ inline void softmax_topk(const float *zs, int zstride, int t0, int nt
         }
     }
     if (__any(any_nan) && (tid & 63) == 0) atomicOr(flags, kFlagNaN);
+}
+
+// MAXQ: the most slices the calling kernel can need (E <= 16*MAXQ there).
+template <int MAXQ = 16>
+__device__ inline void softmax_topk(const float *zs, int zstride, int t0, int nt, int E, int k,
+                                    int32_t *__restrict__ idx_out, float *__restrict__ prob_out,
+                                    float *__restrict__ probs_out, uint32_t *flags,
+                                    int32_t *idx_lds = nullptr) {  // nullable: LDS copy [nt*k] of the chosen indices
+#define PG_SOFTMAX(NQ_) softmax_topk_n<NQ_>(zs, zstride, t0, nt, E, k, idx_out, prob_out, probs_out, flags, idx_lds)
+    if (E <= 16) PG_SOFTMAX(1);  // uniform over the kernel
+    else if (E <= 32) PG_SOFTMAX(2);
+    else if (E <= 64) PG_SOFTMAX(4);
+    else if (MAXQ <= 8 || E <= 128) PG_SOFTMAX(8);
+    else PG_SOFTMAX(16);
+#undef PG_SOFTMAX
 }
 
 template <typename XT>
@@ -270,36 +311,36 @@ __global__ __launch_bounds__(NW * 64) void gate_topk_mfma_kernel(
 #pragma unroll
         for (int q = 0; q < 8; ++q) acc[p][q] = gfloatx4{0.f, 0.f, 0.f, 0.f};
 
-    const bool tok_ok = n < nt;
-    const __bf16 *xrow = x + (size_t)(t0 + (tok_ok ? n : 0)) * d + 8 * g;
+    const __bf16 *xrow = x + (size_t)(t0 + (n < nt ? n : 0)) * d + 8 * g;  // rows past the batch read its first token; their logits are never used
     // Register prefetch ring, PF k-tiles deep: the operands of k-tile i + PF are requested when
     // k-tile i is consumed, so a wavefront pays the memory latency once, not once per k-tile.
-    // Stages past the last k-tile hold zeros (they add nothing).
+    // Every request is an unconditional load from a clamped (always valid) address, so nothing
+    // makes the compiler wait for one load before it issues the next: a stage past the last
+    // k-tile reads the last one again and has its token operand zeroed when it is used (it adds
+    // nothing), column vectors past E read the last real one (their logits are never used).
     constexpr int PF = NP == 1 ? 3 : 2;
     const gbf16x8 zero8 = gbf16x8{0, 0, 0, 0, 0, 0, 0, 0};
     gbf16x8 a_buf[PF], rows_buf[PF][NP][8];
     auto request = [&](int kt, gbf16x8 &a, gbf16x8 (&rows)[NP][8]) {
-        const bool live = kt < KT;
-        a = (live && tok_ok) ? *reinterpret_cast<const gbf16x8 *>(xrow + kt * 32) : zero8;
+        const int ktc = min(kt, KT - 1);
+        a = *reinterpret_cast<const gbf16x8 *>(xrow + ktc * 32);
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
-            const int cv = n + 16 * p;
-            if (live && cv < ncv) {
-                const gbf16x8 *src = reinterpret_cast<const gbf16x8 *>(w + (size_t)(kt * 32 + 8 * g) * E) + cv;
+            const int cv = min(n + 16 * p, ncv - 1);
+            const gbf16x8 *src = reinterpret_cast<const gbf16x8 *>(w + (size_t)(ktc * 32 + 8 * g) * E) + cv;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) rows[p][j] = src[(size_t)j * ncv];
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) rows[p][j] = zero8;
-            }
+            for (int j = 0; j < 8; ++j) rows[p][j] = src[(size_t)j * ncv];
         }
     };
 #pragma unroll
     for (int st = 0; st < PF; ++st) request(wave + NW * st, a_buf[st], rows_buf[st]);
+    // the instruction scheduler must not move these loads down to their uses to save registers
+    // (that would pay the memory latency once per stage): nothing crosses this point
+    __builtin_amdgcn_sched_barrier(0);
     for (int kt0 = wave; kt0 < KT; kt0 += NW * PF) {
 #pragma unroll
         for (int st = 0; st < PF; ++st) {
-            const gbf16x8 a = a_buf[st];
+            const gbf16x8 a = kt0 + NW * st < KT ? a_buf[st] : zero8;
             gbf16x8 cells[NP][8];
 #pragma unroll
             for (int p = 0; p < NP; ++p)
@@ -308,6 +349,7 @@ __global__ __launch_bounds__(NW * 64) void gate_topk_mfma_kernel(
 #pragma unroll
                     for (int j = 0; j < 8; ++j) cells[p][q][j] = rows_buf[st][p][j][q];
             request(kt0 + NW * (st + PF), a_buf[st], rows_buf[st]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int p = 0; p < NP; ++p)
 #pragma unroll
@@ -316,22 +358,17 @@ __global__ __launch_bounds__(NW * 64) void gate_topk_mfma_kernel(
         }
     }
     // lane holds tokens 4*g + r (r = 0..3), column n of product q = expert 8*(n + 16*p) + q.  The
-    // partial logits are parked as [wave][p][q][r][lane] planes (lane-contiguous: no bank conflicts)
-    // and added over the four wavefronts in wave order.
+    // partial logits are parked as [wave][p][q][lane][r] (one 16-byte LDS write per accumulator
+    // tile) and added over the wavefronts in wave order.
 #pragma unroll
     for (int p = 0; p < NP; ++p)
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            float *dst = part + ((((size_t)wave * NP + p) * 8 + q) * 4) * 64 + lane;
-            dst[0 * 64] = acc[p][q].x;
-            dst[1 * 64] = acc[p][q].y;
-            dst[2 * 64] = acc[p][q].z;
-            dst[3 * 64] = acc[p][q].w;
-        }
+        for (int q = 0; q < 8; ++q)
+            reinterpret_cast<gfloatx4 *>(part)[(((size_t)wave * NP + p) * 8 + q) * 64 + lane] = acc[p][q];
     __syncthreads();
     constexpr int PLANE = NP * 8 * 4 * 64;  // floats per wavefront
     for (int o = tid; o < PLANE; o += NT) {
-        const int l = o & 63, r = (o >> 6) & 3, q = (o >> 8) & 7, p = o >> 11;
+        const int r = o & 3, l = (o >> 2) & 63, q = (o >> 8) & 7, p = o >> 11;
         const int e = 8 * ((l & 15) + 16 * p) + q, tokl = 4 * (l >> 4) + r;
         float sum = part[o];
 #pragma unroll
@@ -346,7 +383,7 @@ __global__ __launch_bounds__(NW * 64) void gate_topk_mfma_kernel(
     int32_t *r_idx = reinterpret_cast<int32_t *>(part);      // [n]   (the partial planes are dead by now)
     int32_t *r_cnt = r_idx + GATE_ROUTE_MAX;                 // [E]
     int32_t *r_off = r_cnt + PGMOE_MAX_EXPERTS;              // [E]
-    softmax_topk(zs, ecols, t0, nt, E, k, idx_out, prob_out, probs_out, flags, route ? r_idx : nullptr);
+    softmax_topk<8 * NP>(zs, ecols, t0, nt, E, k, idx_out, prob_out, probs_out, flags, route ? r_idx : nullptr);
     if (!route) return;
     const int n_sel = nt * k;
     __syncthreads();
