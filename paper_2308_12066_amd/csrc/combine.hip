@@ -70,11 +70,27 @@ __global__ __launch_bounds__(256) void combine_partials_kernel(const float *__re
     const bool live = c4 < d / 4;
     const size_t plane4 = (size_t)n_rows * d / 4;
     floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+    // the residual is needed last: request it first, so that its latency is not paid at the end
+    bf16x4 res = bf16x4{0, 0, 0, 0};
+    if (x_next && pl == 0 && live) res = *reinterpret_cast<const bf16x4 *>(x_res + (size_t)t * d + 4 * (size_t)c4);
     for (int j = 0; j < k; ++j) {
         floatx4 s = floatx4{0.f, 0.f, 0.f, 0.f};
         if (live) {
             const floatx4 *src = reinterpret_cast<const floatx4 *>(partial) + (size_t)row_of[(size_t)t * k + j] * (d / 4) + c4;
-            for (int p = pl; p < P; p += PL) s += src[(size_t)p * plane4];
+            // eight partials are requested at a time and then added in ascending order (the order
+            // of ffn_reduce_kernel); a plain loop waits for every load before it issues the next
+            constexpr int U = 8;
+            for (int p0 = pl; p0 < P; p0 += PL * U) {
+                floatx4 v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int p = p0 + u * PL;
+                    v[u] = src[(size_t)(p < P ? p : pl) * plane4];  // past the end: a valid address, value unused
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (p0 + u * PL < P) s += v[u];
+            }
         }
         if (PL > 1) {
             __syncthreads();  // previous round's readers are done with sub
@@ -102,7 +118,7 @@ __global__ __launch_bounds__(256) void combine_partials_kernel(const float *__re
         *reinterpret_cast<bf16x4 *>(y + o) = v;
     }
     if (x_next) {
-        const bf16x4 r = *reinterpret_cast<const bf16x4 *>(x_res + o);
+        const bf16x4 r = res;
         bf16x4 v;
         v.x = (__bf16)((float)r.x + acc.x); v.y = (__bf16)((float)r.y + acc.y);
         v.z = (__bf16)((float)r.z + acc.z); v.w = (__bf16)((float)r.w + acc.w);

@@ -272,6 +272,100 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_vec_kernel(
     softmax_topk(zs, PGMOE_MAX_EXPERTS, t0, nt, E, k, idx_out, prob_out, probs_out, flags);
 }
 
+// Token grouping inside a gate kernel whose single workgroup holds the whole (decode-sized)
+// batch: the same integers as route_kernel (counts, exclusive prefix sum, stable rank, inverse
+// map), from the LDS copy r_idx[n_sel] of the chosen experts.  r_cnt, r_off: LDS [E] each.
+__device__ inline void group_in_workgroup(const int32_t *r_idx, int32_t *r_cnt, int32_t *r_off, int n_sel, int E, int k,
+                                          int n_threads, int32_t *__restrict__ row_of, int32_t *__restrict__ offsets,
+                                          int32_t *__restrict__ src_row) {
+    const int tid = threadIdx.x;
+    __syncthreads();
+    for (int e = tid; e < E; e += n_threads) {
+        int c = 0;
+        for (int i = 0; i < n_sel; ++i) c += r_idx[i] == e ? 1 : 0;
+        r_cnt[e] = c;
+    }
+    __syncthreads();
+    for (int e = tid; e < E; e += n_threads) {
+        int o = 0;
+        for (int q = 0; q < e; ++q) o += r_cnt[q];
+        r_off[e] = o;
+        offsets[e] = o;
+    }
+    if (tid == 0) offsets[E] = n_sel;
+    __syncthreads();
+    for (int i = tid; i < n_sel; i += n_threads) {
+        const int e = r_idx[i];
+        int rank = 0;
+        for (int q = 0; q < i; ++q) rank += r_idx[q] == e ? 1 : 0;
+        const int r = r_off[e] + rank;
+        row_of[i] = r;
+        src_row[r] = i / k;
+    }
+}
+
+// Smallest gates (bf16, at most GS_TOK tokens, 8 or 16 experts: batch-1 decode of the 8-expert
+// models): latency is everything, the arithmetic is a few thousand multiply-adds.  One workgroup;
+// thread i owns rows 8i .. 8i+7 of W (whole rows: E contiguous values) and the matching eight
+// features of every token, all requested at once; partial logits are summed over the 16 lanes
+// of a row by rotation, then over the rows of all wavefronts in LDS in ascending order.
+constexpr int GS_TOK = 4;
+constexpr int GS_THREADS = 256;
+typedef __bf16 gs_bf16x8 __attribute__((ext_vector_type(8)));
+
+template <int EV, int NTOK>  // EV = E / 8 (1 or 2); NTOK = tokens the arithmetic is unrolled for (T <= NTOK <= GS_TOK)
+__global__ __launch_bounds__(GS_THREADS) void gate_small_kernel(
+    const __bf16 *__restrict__ x, const __bf16 *__restrict__ w, const float *__restrict__ bias, int T, int d, int k,
+    int32_t *__restrict__ idx_out, float *__restrict__ prob_out, float *__restrict__ probs_out, uint32_t *flags,
+    int32_t *__restrict__ row_of, int32_t *__restrict__ offsets, int32_t *__restrict__ src_row) {
+    constexpr int E = 8 * EV;
+    constexpr int ROWS = GS_THREADS / 16;                // 16-lane rows in the workgroup
+    __shared__ float part[ROWS][NTOK * E];
+    __shared__ float zs[GS_TOK * 16];
+    __shared__ int32_t r_idx[GS_TOK * E], r_cnt[E], r_off[E];
+    const int tid = threadIdx.x;
+    const bool mine = 8 * tid < d;                       // d <= 8 * GS_THREADS (checked by the host)
+    const int r0 = mine ? 8 * tid : 0;                   // idle threads read rows 0..7 and add nothing
+    const float b = (bias && tid < NTOK * E) ? bias[tid % E] : 0.f;  // needed last, requested first
+    gs_bf16x8 xv[NTOK], wv[8][EV];
+#pragma unroll
+    for (int t = 0; t < NTOK; ++t) xv[t] = *reinterpret_cast<const gs_bf16x8 *>(x + (size_t)(t < T ? t : 0) * d + r0);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int v = 0; v < EV; ++v) wv[j][v] = *reinterpret_cast<const gs_bf16x8 *>(w + (size_t)(r0 + j) * E + 8 * v);
+    float acc[NTOK][E];
+#pragma unroll
+    for (int t = 0; t < NTOK; ++t)
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            float a = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a = fmaf((float)xv[t][j], (float)wv[j][e >> 3][e & 7], a);
+            a = mine ? a : 0.f;
+            acc[t][e] = group_sum(a);
+        }
+    if ((tid & 15) == 0) {
+#pragma unroll
+        for (int t = 0; t < NTOK; ++t)
+#pragma unroll
+            for (int e = 0; e < E; ++e) part[tid >> 4][t * E + e] = acc[t][e];
+    }
+    __syncthreads();
+    if (tid < NTOK * E) {
+        const int e = tid % E;
+        float sum = part[0][tid];
+#pragma unroll
+        for (int r = 1; r < ROWS; ++r) sum += part[r][tid];
+        zs[(tid / E) * 16 + e] = sum + b;
+    }
+    __syncthreads();
+    const bool route = row_of != nullptr;
+    softmax_topk_n<1>(zs, 16, 0, T, E, k, idx_out, prob_out, probs_out, flags, route ? r_idx : nullptr);
+    if (!route) return;
+    group_in_workgroup(r_idx, r_cnt, r_off, T * k, E, k, GS_THREADS, row_of, offsets, src_row);
+}
+
 // Matrix-core path (bf16, E a multiple of 8, d_model a multiple of 32): the gate is a skinny
 // GEMM [T,d] x [d,E].  A workgroup takes 16 tokens (one matrix-core tile); its NW wavefronts
 // (eight for E <= 128, four above) split the d_model reduction (k-tile kt goes to wavefront
@@ -385,30 +479,7 @@ __global__ __launch_bounds__(NW * 64) void gate_topk_mfma_kernel(
     int32_t *r_off = r_cnt + PGMOE_MAX_EXPERTS;              // [E]
     softmax_topk<8 * NP>(zs, ecols, t0, nt, E, k, idx_out, prob_out, probs_out, flags, route ? r_idx : nullptr);
     if (!route) return;
-    const int n_sel = nt * k;
-    __syncthreads();
-    for (int e = tid; e < E; e += NT) {
-        int c = 0;
-        for (int i = 0; i < n_sel; ++i) c += r_idx[i] == e ? 1 : 0;
-        r_cnt[e] = c;
-    }
-    __syncthreads();
-    for (int e = tid; e < E; e += NT) {
-        int o = 0;
-        for (int q = 0; q < e; ++q) o += r_cnt[q];
-        r_off[e] = o;
-        offsets[e] = o;
-    }
-    if (tid == 0) offsets[E] = n_sel;
-    __syncthreads();
-    for (int i = tid; i < n_sel; i += NT) {
-        const int e = r_idx[i];
-        int rank = 0;
-        for (int q = 0; q < i; ++q) rank += r_idx[q] == e ? 1 : 0;
-        const int r = r_off[e] + rank;
-        row_of[i] = r;
-        src_row[r] = i / k;
-    }
+    group_in_workgroup(r_idx, r_cnt, r_off, nt * k, E, k, NT, row_of, offsets, src_row);
 }
 
 template <typename XT>
@@ -442,6 +513,23 @@ static int launch_gate_mfma(pgmoe_ctx *ctx, const __bf16 *x, const __bf16 *w, co
     const bool route = row_of && offsets && src_row && grid.x == 1 && T * c.top_k <= GATE_ROUTE_MAX;
     if (!route) row_of = offsets = src_row = nullptr;
     if (routed) *routed = route;
+    if (T <= GS_TOK && (c.n_experts == 8 || c.n_experts == 16) && c.d_model <= 8 * GS_THREADS && !getenv("PGMOE_GATE_NO_SMALL")) {
+#define PG_GATE_SMALL(EV_, NTOK_)                                                                                            \
+    hipLaunchKernelGGL((gate_small_kernel<EV_, NTOK_>), dim3(1), dim3(GS_THREADS), 0, s, x, w, bias, T, c.d_model, c.top_k, idx, \
+                       prob, probs, ctx->dev_flags, row_of, offsets, src_row)
+        if (c.n_experts == 8) {
+            if (T == 1) PG_GATE_SMALL(1, 1);
+            else if (T == 2) PG_GATE_SMALL(1, 2);
+            else PG_GATE_SMALL(1, 4);
+        } else {
+            if (T == 1) PG_GATE_SMALL(2, 1);
+            else if (T == 2) PG_GATE_SMALL(2, 2);
+            else PG_GATE_SMALL(2, 4);
+        }
+#undef PG_GATE_SMALL
+        PG_HIP(ctx, hipGetLastError());
+        return PGMOE_OK;
+    }
     // eight wavefronts split d_model: with a three-deep prefetch ring each of them has all its
     // k-tiles (d_model <= 768) in flight at once, i.e. the kernel pays the memory latency once
 #define PG_GATE_MFMA(NP_, NW_)                                                                                          \

@@ -49,6 +49,8 @@ GATE_CASES = [
     ("f32", 32, 64, 8, 1), ("f32", 37, 100, 5, 2), ("f32", 9, 1500, 12, 3), ("bf16", 1, 768, 8, 1),
     ("bf16", 16, 768, 64, 1), ("bf16", 64, 1024, 128, 2), ("bf16", 333, 768, 128, 1), ("bf16", 7, 256, 256, 4),
     ("bf16", 8, 64, 100, 100), ("f32", 5, 64, 1, 1), ("bf16", 20, 2048, 16, 2),
+    # the smallest gates (at most 4 tokens, 8 or 16 experts) have a kernel of their own
+    ("bf16", 4, 768, 8, 2), ("bf16", 3, 2048, 16, 16), ("bf16", 1, 64, 16, 1), ("bf16", 2, 1024, 8, 8), ("bf16", 5, 768, 8, 1),
 ]
 
 
@@ -88,16 +90,19 @@ def test_gate_topk_matches_oracle(hx, dtype, T, d, E, k):
     ctx.close()
 
 
-def test_gate_ties_go_to_lowest_index_and_nan_is_flagged(hx):
+@pytest.mark.parametrize("dtype,T", [("f32", 6), ("bf16", 6), ("bf16", 3)])   # plain, matrix-core and smallest-gate kernel
+def test_gate_ties_go_to_lowest_index_and_nan_is_flagged(hx, dtype, T):
     H, B = hx
-    T, d, E, k = 6, 64, 16, 3
-    w = small_workload("f32", T, d, 8, E, k)
+    d, E, k = 64, 16, 3
+    w = small_workload(dtype, T, d, 64, E, k)
     ctx = B.Context(H.config_for(w))
     x = np.random.default_rng(5).standard_normal((T, d)).astype(np.float32)
+    if dtype == "bf16":
+        x = W.round_to_bf16(x)
     wg = np.zeros((d, E), dtype=np.float32)
     idx = torch.zeros((T, k), dtype=torch.int32, device="cuda")
     prob = torch.zeros((T, k), dtype=torch.float32, device="cuda")
-    ctx.pregate_topk(H.to_device(x, "f32"), H.to_device(wg, "f32"), None, T, idx, prob)
+    ctx.pregate_topk(H.to_device(x, dtype), H.to_device(wg, dtype), None, T, idx, prob)
     torch.cuda.synchronize()
     assert np.array_equal(idx.cpu().numpy(), np.tile(np.arange(k, dtype=np.int32), (T, 1)))
     assert np.all(prob.cpu().numpy() == np.float32(1.0 / E))
@@ -106,7 +111,7 @@ def test_gate_ties_go_to_lowest_index_and_nan_is_flagged(hx):
     bias = np.zeros(E, dtype=np.float32)
     bias[2] = np.nan
     bias[7] = 1.0
-    ctx.pregate_topk(H.to_device(x, "f32"), H.to_device(wg, "f32"), torch.from_numpy(bias).cuda(), T, idx, prob)
+    ctx.pregate_topk(H.to_device(x, dtype), H.to_device(wg, dtype), torch.from_numpy(bias).cuda(), T, idx, prob)
     torch.cuda.synchronize()
     o = R.gate(x, wg, bias, k)
     assert np.array_equal(idx.cpu().numpy(), o["idx"]) and o["idx"][0].tolist() == [7, 0, 1]
