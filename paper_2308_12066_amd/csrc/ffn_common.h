@@ -22,12 +22,20 @@ struct ChunkInfo {
     int expert, slot, row0, nrows;  // nrows == 0: chunk does not exist
 };
 
-__device__ inline int wave_incl_scan(int v, int lane) {
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(v, off);
-        if (lane >= off) v += o;
-    }
+// Inclusive prefix sum over the 64 lanes of a wavefront (all of them active) with data-parallel
+// primitives: four shifts inside each row of 16 lanes, then lane 15 of row 0 / 2 into row 1 / 3
+// and lane 31 into rows 2 and 3.  Six VALU operations instead of six trips through the LDS crossbar.
+template <int CTRL, int ROW_MASK>
+__device__ inline int dpp_or_zero(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);  // lanes without a source get 0
+}
+__device__ inline int wave_incl_scan(int v) {
+    v += dpp_or_zero<0x111, 0xf>(v);  // row_shr:1
+    v += dpp_or_zero<0x112, 0xf>(v);  // row_shr:2
+    v += dpp_or_zero<0x114, 0xf>(v);  // row_shr:4
+    v += dpp_or_zero<0x118, 0xf>(v);  // row_shr:8
+    v += dpp_or_zero<0x142, 0xa>(v);  // row_bcast:15 -> rows 1 and 3
+    v += dpp_or_zero<0x143, 0xc>(v);  // row_bcast:31 -> rows 2 and 3
     return v;
 }
 
@@ -44,21 +52,21 @@ __device__ inline ChunkInfo find_chunk(const int32_t *__restrict__ offsets, int 
         }
         const int c = (n + rows_per_chunk - 1) / rows_per_chunk;
         const int nz = n > 0 ? 1 : 0;
-        const int c_incl = wave_incl_scan(c, lane), nz_incl = wave_incl_scan(nz, lane);
+        const int c_incl = wave_incl_scan(c), nz_incl = wave_incl_scan(nz);
         const int c_excl = chunk_base + c_incl - c;
         const bool mine = chunk >= c_excl && chunk < c_excl + c;
         const unsigned long long hit = __ballot(mine);
         if (hit) {
-            const int src = __ffsll((long long)hit) - 1;
-            const int first = (chunk - __shfl(c_excl, src)) * rows_per_chunk;
+            const int src = __ffsll((long long)hit) - 1;  // uniform: read that lane's values directly
+            const int first = (chunk - __builtin_amdgcn_readlane(c_excl, src)) * rows_per_chunk;
             ci.expert = q * 64 + src;
-            ci.slot = slot_base + __shfl(nz_incl, src) - 1;
-            ci.row0 = __shfl(lo, src) + first;
-            ci.nrows = min(rows_per_chunk, __shfl(n, src) - first);
+            ci.slot = slot_base + __builtin_amdgcn_readlane(nz_incl, src) - 1;
+            ci.row0 = __builtin_amdgcn_readlane(lo, src) + first;
+            ci.nrows = min(rows_per_chunk, __builtin_amdgcn_readlane(n, src) - first);
             return ci;
         }
-        chunk_base += __shfl(c_incl, 63);
-        slot_base += __shfl(nz_incl, 63);
+        chunk_base += __builtin_amdgcn_readlane(c_incl, 63);
+        slot_base += __builtin_amdgcn_readlane(nz_incl, 63);
     }
     return ci;
 }
@@ -70,7 +78,7 @@ __device__ inline int count_chunks(const int32_t *__restrict__ offsets, int E, i
     for (int q = 0; q * 64 < E; ++q) {
         const int e = q * 64 + lane;
         const int n = e < E ? offsets[e + 1] - offsets[e] : 0;
-        total += __shfl(wave_incl_scan((n + rows_per_chunk - 1) / rows_per_chunk, lane), 63);
+        total += __builtin_amdgcn_readlane(wave_incl_scan((n + rows_per_chunk - 1) / rows_per_chunk), 63);
     }
     return total;
 }
