@@ -75,6 +75,7 @@ __global__ __launch_bounds__(256) void combine_partials_kernel(const float *__re
     if (x_next && pl == 0 && live) res = *reinterpret_cast<const bf16x4 *>(x_res + (size_t)t * d + 4 * (size_t)c4);
     for (int j = 0; j < k; ++j) {
         floatx4 s = floatx4{0.f, 0.f, 0.f, 0.f};
+        const float p_j = prob[(size_t)t * k + j];  // used after the reduction: requested with the row index
         if (live) {
             const floatx4 *src = reinterpret_cast<const floatx4 *>(partial) + (size_t)row_of[(size_t)t * k + j] * (d / 4) + c4;
             // eight partials are requested at a time and then added in ascending order (the order
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(256) void combine_partials_kernel(const float *__re
             }
         }
         if (pl == 0) {
-            const float p = prob[(size_t)t * k + j];
+            const float p = p_j;
             acc.x = fmaf(p, (float)(__bf16)s.x, acc.x);
             acc.y = fmaf(p, (float)(__bf16)s.y, acc.y);
             acc.z = fmaf(p, (float)(__bf16)s.z, acc.z);
