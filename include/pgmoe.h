@@ -281,6 +281,21 @@ int pgmoe_set_schedule(pgmoe_ctx *ctx, int schedule);
  * reads, whichever comes first.  0 <= microseconds <= 100000. */
 int pgmoe_set_nonmoe_standin(pgmoe_ctx *ctx, float microseconds);
 
+/* Diagnostic for pgmoe_stack_step's streams.  HIP maps streams onto a small number of hardware
+ * queues (4 by default) and two streams that share one run their kernels in submission order:
+ * the migration then silently serialises against the compute stream, or two consecutive
+ * migrations against each other, and the step gets slower without any error.  This call starts a
+ * clock-watching kernel of 200 us on two streams at a time and reports, as a bit mask in
+ * *shared_out (host), which pairs did NOT run side by side.  The context's own copy stream is
+ * replaced (up to 6 times) until it shares a queue with neither of the caller's streams; a caller
+ * whose own two streams share one should pick another copy stream and ask again.  Synchronises
+ * the device; call it at set-up, not in the hot path.  compute_stream == copy_stream (everything
+ * in line) reports PGMOE_STREAMS_COMPUTE_COPY by definition. */
+#define PGMOE_STREAMS_COMPUTE_COPY 1 /* the caller's compute and copy stream */
+#define PGMOE_STREAMS_COMPUTE_OWN 2  /* the caller's compute stream and the context's own copy stream */
+#define PGMOE_STREAMS_COPY_OWN 4     /* the caller's copy stream and the context's own copy stream */
+int pgmoe_check_streams(pgmoe_ctx *ctx, void *compute_stream, void *copy_stream, int *shared_out);
+
 typedef struct {
     const void *const *gate_w;  /* host [L] -> dev [d,E] */
     const float *const *gate_b; /* host [L] -> dev [E] | NULL; may itself be NULL */

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(HERE, "libpgmoe.so")
 
 OK, EINVAL, ENOTPINNED, ENOSLOT, EBADINDEX, EHIP, ENODEVICE, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7
 F32, BF16 = 0, 1
+STREAMS_COMPUTE_COPY, STREAMS_COMPUTE_OWN, STREAMS_COPY_OWN = 1, 2, 4
 FLAG_HOST_ONLY = 1
 FLAG_FETCH_MEMCPY = 2
 SCHED_PREGATED, SCHED_ON_DEMAND, SCHED_PREFETCH_ALL = 0, 1, 2
@@ -29,7 +30,7 @@ EXPORTS = [
     "pgmoe_register_resident_experts", "pgmoe_fetch_experts", "pgmoe_get_fetch_stats", "pgmoe_unique_experts",
     "pgmoe_permute", "pgmoe_expert_ffn", "pgmoe_combine", "pgmoe_stack_step", "pgmoe_device_flags",
     "pgmoe_ffn_timing_begin", "pgmoe_ffn_timing_end", "pgmoe_slot_address", "pgmoe_fetch_timing", "pgmoe_trace", "pgmoe_get_block_trace", "pgmoe_fetch_all_experts", "pgmoe_set_schedule",
-    "pgmoe_ffn_kernel_name", "pgmoe_set_nonmoe_standin",
+    "pgmoe_ffn_kernel_name", "pgmoe_set_nonmoe_standin", "pgmoe_check_streams",
 ]
 
 
@@ -104,6 +105,7 @@ def _load():
     L.pgmoe_fetch_all_experts.argtypes = [vp, i, vp, vp]
     L.pgmoe_set_schedule.argtypes = [vp, i]
     L.pgmoe_set_nonmoe_standin.argtypes = [vp, c_float]
+    L.pgmoe_check_streams.argtypes = [vp, vp, vp, POINTER(c_int)]
     L.pgmoe_get_block_trace.argtypes = [vp, i, POINTER(BlockTrace)]
     L.pgmoe_slot_address.argtypes = [vp, i, i, POINTER(vp)]
     L.pgmoe_ffn_timing_end.argtypes = [vp, POINTER(c_int), POINTER(c_float), POINTER(c_float)]
@@ -292,6 +294,12 @@ class Context:
 
     def set_schedule(self, schedule: int):
         self._check(lib.pgmoe_set_schedule(self._h, schedule))
+
+    def check_streams(self, compute_stream, copy_stream) -> int:
+        """Bit mask of the stream pairs that share a hardware queue (STREAMS_*); 0 = all side by side."""
+        shared = c_int(0)
+        self._check(lib.pgmoe_check_streams(self._h, _stream(compute_stream), _stream(copy_stream), byref(shared)))
+        return shared.value
 
     def set_nonmoe_standin(self, microseconds: float):
         self._check(lib.pgmoe_set_nonmoe_standin(self._h, microseconds))

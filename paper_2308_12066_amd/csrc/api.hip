@@ -251,6 +251,8 @@ int pgmoe_destroy(pgmoe_ctx *c) {
         if (c->idx_ready) (void)hipEventDestroy(c->idx_ready);
         if (c->step_start) (void)hipEventDestroy(c->step_start);
         if (c->copy2) (void)hipStreamDestroy(c->copy2);
+        for (hipStream_t sp : c->spare_streams)
+            if (sp) (void)hipStreamDestroy(sp);
         for (int g = 0; g < kGen; ++g) {
             if (c->fetch_done[g]) (void)hipEventDestroy(c->fetch_done[g]);
             if (c->ffn_done[g]) (void)hipEventDestroy(c->ffn_done[g]);

@@ -417,6 +417,63 @@ static int launch_standin(pgmoe_ctx *ctx, void *stream) {
     return PGMOE_OK;
 }
 
+// Do kernels on streams a and b run side by side?  One clock-watching kernel of `us` microseconds
+// on each, started together: side by side they take about `us`, on a shared hardware queue 2 * us.
+static int streams_run_side_by_side(pgmoe_ctx *ctx, hipStream_t a, hipStream_t b, float us, bool *yes) {
+    const unsigned long long ticks = (unsigned long long)(us * 100.f);
+    PG_HIP(ctx, hipDeviceSynchronize());
+    const auto t0 = std::chrono::steady_clock::now();
+    hipLaunchKernelGGL(nonmoe_standin_kernel, dim3(1), dim3(64), 0, a, ticks, ticks * 10ull + 1000ull);
+    hipLaunchKernelGGL(nonmoe_standin_kernel, dim3(1), dim3(64), 0, b, ticks, ticks * 10ull + 1000ull);
+    PG_HIP(ctx, hipGetLastError());
+    PG_HIP(ctx, hipStreamSynchronize(a));
+    PG_HIP(ctx, hipStreamSynchronize(b));
+    const float took = std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - t0).count();
+    *yes = took < 1.6f * us;
+    return PGMOE_OK;
+}
+
+int pgmoe_check_streams(pgmoe_ctx *ctx, void *compute_stream, void *copy_stream, int *shared_out) {
+    const char *fn = "pgmoe_check_streams";
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
+    if (!shared_out) return fail(ctx, PGMOE_EINVAL, "%s: shared_out is NULL", fn);
+    if (ctx->host_only) return fail(ctx, PGMOE_ENODEVICE, "%s: context is host-only, nothing can be launched", fn);
+    hipStream_t cs = (hipStream_t)compute_stream, ps = (hipStream_t)copy_stream;
+    const float us = 200.f;
+    int shared = 0;
+    bool ok = true;
+    hipLaunchKernelGGL(nonmoe_standin_kernel, dim3(1), dim3(64), 0, cs, 100ull, 2000ull);  // first launch loads the code: not timed
+    PG_HIP(ctx, hipGetLastError());
+    // the context's own copy stream first: it is replaced until it shares a queue with neither of
+    // the caller's streams (the old ones are kept until pgmoe_destroy, so that a new stream does
+    // not simply get the queue that was just given back)
+    for (int attempt = 0;; ++attempt) {
+        shared = 0;
+        int rc = streams_run_side_by_side(ctx, cs, ctx->copy2, us, &ok);
+        if (rc) return rc;
+        if (!ok) shared |= PGMOE_STREAMS_COMPUTE_OWN;
+        if (ps != cs) {
+            rc = streams_run_side_by_side(ctx, ps, ctx->copy2, us, &ok);
+            if (rc) return rc;
+            if (!ok) shared |= PGMOE_STREAMS_COPY_OWN;
+        }
+        if (!shared || attempt == kSpareStreams) break;
+        hipStream_t fresh = nullptr;
+        PG_HIP(ctx, hipStreamCreateWithFlags(&fresh, hipStreamNonBlocking));
+        ctx->spare_streams[attempt] = ctx->copy2;
+        ctx->copy2 = fresh;
+    }
+    if (ps == cs) {
+        shared |= PGMOE_STREAMS_COMPUTE_COPY;
+    } else {
+        int rc = streams_run_side_by_side(ctx, cs, ps, us, &ok);
+        if (rc) return rc;
+        if (!ok) shared |= PGMOE_STREAMS_COMPUTE_COPY;
+    }
+    *shared_out = shared;
+    return PGMOE_OK;
+}
+
 // The gate that routes block g, evaluated on hidden state x, inside pgmoe_stack_step.  For a
 // decode-sized bf16 batch the gate kernel also groups block g's tokens by expert (offsets, row_of,
 // inverse map) and routed[g] says so; pgmoe_stack_step has validated the buffers.

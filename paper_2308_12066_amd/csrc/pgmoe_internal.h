@@ -15,6 +15,7 @@ namespace pgmoe {
 enum StoreMode { STORE_NONE = 0, STORE_HOST = 1, STORE_RESIDENT = 2 };
 
 constexpr int kGen = PGMOE_MAX_PREGATE_DISTANCE + 1;  // most block generations resident at once
+constexpr int kSpareStreams = 6;  // most replacements of the context's own copy stream (pgmoe_check_streams)
 
 // Device-side sticky condition bits (see pgmoe_device_flags).
 constexpr uint32_t kFlagNaN = 1u;
@@ -76,6 +77,7 @@ struct pgmoe_ctx {
     hipStream_t ffn_stream[pgmoe::kGen];    // stream the generation's last FFN ran on
     hipStream_t fetch_stream[pgmoe::kGen];  // stream the generation's last fetch ran on
     hipStream_t copy2;                      // internal second copy stream
+    hipStream_t spare_streams[pgmoe::kSpareStreams] = {};  // earlier ones that shared a hardware queue with a caller's stream
     bool gen_all[pgmoe::kGen];              // generation holds every expert of its block (slot = expert id)
     bool gen_table[pgmoe::kGen];            // generation was filled through the expert cache: FFN reads dev_table
 

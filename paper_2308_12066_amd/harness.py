@@ -117,6 +117,14 @@ class Stack:
         self.workspace = torch.zeros(self.ctx.workspace_bytes, dtype=torch.uint8, device=dev)
         self.compute = torch.cuda.Stream()
         self.copy = torch.cuda.Stream()
+        # streams that share a hardware queue would serialise migration and compute without any
+        # error: ask the library, and take another copy stream while ours shares one with compute
+        self.shared_streams = self.ctx.check_streams(self.compute, self.copy)
+        for _ in range(8):
+            if not self.shared_streams & B.STREAMS_COMPUTE_COPY:
+                break
+            self.copy = torch.cuda.Stream()
+            self.shared_streams = self.ctx.check_streams(self.compute, self.copy)
         if w.offloaded:
             self.ctx.register_host_experts(store.host, store.expert_stride, store.block_stride)
         else:

@@ -143,6 +143,17 @@ def test_pack_is_the_documented_permutation_and_unpack_inverts_it(d, f):
     assert np.array_equal(u1, w1) and np.array_equal(u2, w2)
 
 
+def test_check_streams_validates_before_it_launches():
+    c = B.Context(cfg())
+    out = ctypes.c_int(0)
+    assert B.lib.pgmoe_check_streams(None, None, None, ctypes.byref(out)) == B.EINVAL
+    assert B.lib.pgmoe_check_streams(c._h, None, None, None) == B.EINVAL
+    with pytest.raises(B.PgmoeError) as ei:
+        c.check_streams(None, None)
+    assert ei.value.code == B.ENODEVICE
+    c.close()
+
+
 def test_nonmoe_standin_setter_validates_its_argument():
     c = B.Context(cfg())
     c.set_nonmoe_standin(0.0)
