@@ -34,7 +34,7 @@ FLAGS = [
 def _compile(src: str, force: bool) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
     path = os.path.join(CSRC, src)
-    deps = [path, os.path.join(CSRC, "pgmoe_internal.h"), os.path.join(CSRC, "ffn_common.h"), os.path.join(ROOT, "include", "pgmoe.h")]
+    deps = [path, os.path.join(CSRC, "pgmoe_internal.h"), os.path.join(CSRC, "ffn_common.h"), os.path.join(CSRC, "gate_small.h"), os.path.join(ROOT, "include", "pgmoe.h")]
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
     subprocess.run([HIPCC, *FLAGS, "-c", path, "-o", obj], check=True)

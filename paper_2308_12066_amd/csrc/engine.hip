@@ -362,7 +362,8 @@ int pgmoe_slot_address(pgmoe_ctx *ctx, int block, int slot, void **dev_out) {
 // (keep_partials != NULL; see launch_ffn), which pgmoe_stack_step feeds to the fused combine.
 static int expert_ffn_impl(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_t *expert_offsets, int n_rows,
                            void *y_perm, void *workspace, void *stream, int *keep_partials,
-                           const int32_t *src_row = nullptr) {  // src_row: x_perm holds the un-grouped rows (see launch_ffn)
+                           const int32_t *src_row = nullptr,  // src_row: x_perm holds the un-grouped rows (see launch_ffn)
+                           const FusedGate *gate = nullptr, bool *gate_done = nullptr) {  // resident store only (see launch_ffn)
     const char *fn = "pgmoe_expert_ffn";
     if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
     int rc = check_block(ctx, fn, block);
@@ -378,7 +379,7 @@ static int expert_ffn_impl(pgmoe_ctx *ctx, int block, const void *x_perm, const 
     if (ctx->store_mode == STORE_RESIDENT)
         return launch_ffn(ctx, ctx->store_base + (size_t)block * ctx->block_stride, ctx->expert_stride, false,
                           ctx->cfg.n_experts, x_perm, expert_offsets, n_rows, y_perm, workspace, s, keep_partials, nullptr,
-                          src_row);
+                          src_row, gate, gate_done);
     const int gen = block % ctx->n_gen;
     if (ctx->fetched_block[gen] != block)
         return fail(ctx, PGMOE_ESTATE, "%s: block %d was not fetched (generation holds block %d)", fn, block, ctx->fetched_block[gen]);
@@ -501,8 +502,10 @@ static int gate_for_block(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int g, c
 // kernels read their rows of x through that map, so the gather kernel and the x_perm round trip
 // are skipped (same values, hence the same results as pgmoe_permute + pgmoe_expert_ffn).
 static int group_and_run_experts(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int block, int T, const void *x,
-                                 const int32_t *idx, int32_t *row_of, int32_t *offs, void *stream, int *n_partial) {
+                                 const int32_t *idx, int32_t *row_of, int32_t *offs, void *stream, int *n_partial,
+                                 const FusedGate *gate = nullptr, bool *gate_done = nullptr) {
     const int nk = T * ctx->cfg.top_k;
+    if (gate_done) *gate_done = false;
     if (ctx->cfg.dtype != PGMOE_BF16) {
         int rc = pgmoe_permute(ctx, x, idx, T, io->x_perm, row_of, offs, stream);
         if (rc) return rc;
@@ -513,7 +516,7 @@ static int group_and_run_experts(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, i
         int rc = launch_route(ctx, idx, T, row_of, offs, src_row, (hipStream_t)stream);
         if (rc) return rc;
     }
-    return expert_ffn_impl(ctx, block, x, offs, nk, io->y_perm, io->workspace, stream, n_partial, src_row);
+    return expert_ffn_impl(ctx, block, x, offs, nk, io->y_perm, io->workspace, stream, n_partial, src_row, gate, gate_done);
 }
 
 int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *compute_stream, void *copy_stream) {
@@ -607,6 +610,11 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     // queued back to back on the copy stream: the link never idles between them.
     const int N = ctx->distance;
     const int head = std::min(N, L - 1);
+    // Resident store, pre-gate distance 1: nothing waits for a routing, so the pre-gate evaluated
+    // on x_i is offered to block i's expert launch, which carries it as one extra workgroup when
+    // it is a decode-sized launch with one of the smallest gates (one launch fewer per block);
+    // a launch that cannot leaves it to a gate launch of its own right behind it.
+    const bool carry_gate = ctx->store_mode == STORE_RESIDENT && N == 1 && c.dtype == PGMOE_BF16;
     if (ctx->pull_seq >= 0 && N == 1 && c.dtype == PGMOE_BF16) {
         // Block 0's fetch is exposed whatever is done, so it runs on the compute stream itself,
         // right behind its gate: no stream hand-over (11-13 us) before the link starts working,
@@ -632,7 +640,7 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
             if (rc) return rc;
         }
     } else {
-        for (int g = 0; g <= head; ++g) {
+        for (int g = 0; g <= (carry_gate ? 0 : head); ++g) {
             rc = gate_for_block(ctx, io, g, x_at(0), T, compute_stream);
             if (rc) return rc;
             rc = pgmoe_fetch_experts(ctx, g, idx_at(g), T, compute_stream, copy_stream, nullptr);
@@ -643,7 +651,7 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     for (int i = 0; i < L; ++i) {
         if (ctx->trace && i > 0) PG_HIP(ctx, hipEventRecord(ctx->ev_c0[i], (hipStream_t)compute_stream));
         // the pre-gate of block i routes block i+N; its experts start moving before block i executes
-        if (i > 0 && i + N < L) {
+        if (!carry_gate && i > 0 && i + N < L) {
             const int g = i + N;
             rc = gate_for_block(ctx, io, g, x_at(i), T, compute_stream);
             if (rc) return rc;
@@ -655,7 +663,22 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
         // grouping + FFN, then the weighted combine; when the FFN left float32 partial sums, the
         // combine kernel adds them itself (same order as the stand-alone reduction) and y_perm is skipped
         int n_partial = 0;
-        rc = group_and_run_experts(ctx, io, i, T, x_at(i), idx_at(i), row_of, offs, compute_stream, &n_partial);
+        const int g = i + N;
+        if (carry_gate && g < L) {
+            const float *bias = io->gate_b ? io->gate_b[g] : nullptr;
+            if (!aligned(x_at(i), 16) || !aligned(io->gate_w[g], 16) || !aligned(bias, 4))
+                return fail(ctx, PGMOE_EINVAL, "%s: misaligned hidden state, gate weight or bias of block %d", fn, g);
+            const FusedGate fg = {x_at(i), io->gate_w[g], bias, T, idx_at(g), prob_at(g), io->row_of + (size_t)g * nk,
+                                  io->expert_offsets + (size_t)g * (c.n_experts + 1),
+                                  ctx->dev_src_row + (size_t)g * c.max_tokens * c.top_k};
+            bool carried = false;
+            rc = group_and_run_experts(ctx, io, i, T, x_at(i), idx_at(i), row_of, offs, compute_stream, &n_partial, &fg, &carried);
+            if (rc) return rc;
+            if (carried) ctx->routed[g] = true;  // the smallest-gate code groups the tokens as well
+            else rc = gate_for_block(ctx, io, g, x_at(i), T, compute_stream);
+        } else {
+            rc = group_and_run_experts(ctx, io, i, T, x_at(i), idx_at(i), row_of, offs, compute_stream, &n_partial);
+        }
         if (rc) return rc;
         void *y = io->y_blocks ? (char *)io->y_blocks + (size_t)i * xbytes : nullptr;
         if (n_partial > 0)

@@ -24,6 +24,7 @@
 //
 // f32 path - plain float32 kernels (correctness configuration; no matrix cores).
 #include "ffn_common.h"
+#include "gate_small.h"
 
 namespace pgmoe {
 
@@ -183,6 +184,17 @@ __global__ __launch_bounds__(NW * 64) void ffn_fused_kernel(
     }
 }
 
+// The pre-gate a decode-sized launch carries (FusedGate with the types the kernel needs).
+struct DecodeGate {
+    const __bf16 *x, *w;
+    const float *bias;
+    int T, k, E;
+    int32_t *idx;
+    float *prob;
+    uint32_t *flags;
+    int32_t *row_of, *offsets, *src_row;
+};
+
 // Decode-sized variant (at most a few experts active, <= 16 rows each): one workgroup of four
 // wavefronts per (chunk, 32-column sub-slab of d_ff), every weight tile it needs requested before
 // anything else happens, so the kernel is one round of memory latency deep instead of a ring of
@@ -198,8 +210,15 @@ __global__ __launch_bounds__(256) void ffn_decode_kernel(
     const __bf16 *__restrict__ x_perm, const int32_t *__restrict__ offsets, int E, int f,
     const char *__restrict__ w_base, size_t w_stride, int slot_by_rank, int n_slots,
     const unsigned long long *__restrict__ table, float *__restrict__ partial, int n_rows,
-    const int32_t *__restrict__ src_row) {  // nullable: grouped row r is row src_row[r] of x_perm
+    const int32_t *__restrict__ src_row,  // nullable: grouped row r is row src_row[r] of x_perm
+    DecodeGate gate) {            // gate.x != nullptr: workgroup (0, gridDim.y - 1) runs that gate instead of a sub-slab
     constexpr int d = KT * 32;
+    if (gate.x != nullptr && blockIdx.y == gridDim.y - 1) {  // uniform over the workgroup
+        if (blockIdx.x == 0)
+            gate_small_dispatch(gate.E, gate.x, gate.w, gate.bias, gate.T, d, gate.k, gate.idx, gate.prob, nullptr, gate.flags,
+                                gate.row_of, gate.offsets, gate.src_row);
+        return;
+    }
     constexpr int NTD = KT * 2;   // output n-tiles
     constexpr int NA = KT / 2;    // phase-A tiles per wavefront
     constexpr int NB = NTD / 4;   // phase-B tiles per wavefront
@@ -522,9 +541,10 @@ static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, si
 
 int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots, const void *x_perm,
                const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s, int *keep_partials,
-               const unsigned long long *table, const int32_t *src_row) {
+               const unsigned long long *table, const int32_t *src_row, const FusedGate *gate, bool *gate_done) {
     const pgmoe_config &c = ctx->cfg;
     if (keep_partials) *keep_partials = 0;
+    if (gate_done) *gate_done = false;
     if (n_rows == 0) return PGMOE_OK;
     if (c.dtype == PGMOE_F32) {
         float *h = (float *)workspace;
@@ -552,14 +572,21 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
             return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: %d partial sums of %d rows do not fit the workspace", p.n_partial, n_rows);
         const int tslot = ffn_timing_slot(ctx);
         if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_begin[tslot], s));
-        const dim3 grid(p.max_chunks, p.n_partial);
+        // one more row of workgroups for the pre-gate this launch carries, if it is one the smallest-gate code serves
+        DecodeGate dg = {};
+        if (gate && gate_done && gate_small_applies(c, gate->T) && !getenv("PGMOE_FFN_NO_GATE")) {
+            dg = DecodeGate{(const __bf16 *)gate->x, (const __bf16 *)gate->w, gate->bias, gate->T, c.top_k, c.n_experts, gate->idx,
+                            gate->prob, ctx->dev_flags, gate->row_of, gate->offsets, gate->src_row};
+            *gate_done = true;
+        }
+        const dim3 grid(p.max_chunks, p.n_partial + (dg.x ? 1 : 0));
         const size_t lds = (size_t)kt * 1024 + 4096;
         if (kt == 24)
             hipLaunchKernelGGL(ffn_decode_kernel<24>, grid, dim3(256), lds, s, (const __bf16 *)x_perm, offsets, c.n_experts, c.d_ff,
-                               w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, partial, n_rows, src_row);
+                               w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, partial, n_rows, src_row, dg);
         else
             hipLaunchKernelGGL(ffn_decode_kernel<32>, grid, dim3(256), lds, s, (const __bf16 *)x_perm, offsets, c.n_experts, c.d_ff,
-                               w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, partial, n_rows, src_row);
+                               w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, partial, n_rows, src_row, dg);
         PG_HIP(ctx, hipGetLastError());
         if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_end[tslot], s));
         if (keep_partials) {

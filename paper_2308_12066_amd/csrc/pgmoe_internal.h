@@ -145,12 +145,26 @@ int launch_permute(pgmoe_ctx *ctx, const void *x, const int32_t *idx, int T, voi
 // The integer half of launch_permute; src_row (nullable) receives the inverse map grouped row -> token.
 int launch_route(pgmoe_ctx *ctx, const int32_t *idx, int T, int32_t *row_of, int32_t *offsets, int32_t *src_row,
                  hipStream_t s);
+// A pre-gate that an expert-FFN launch may carry as one extra workgroup (Sec. IV-B: the pre-gate
+// of block i is evaluated on the same hidden state as block i's experts and needs nothing from
+// them, so the two can run side by side in one launch).  Only decode-sized launches do it.
+struct FusedGate {
+    const void *x;                  // [T, d] hidden state the gate is evaluated on
+    const void *w;                  // [d, E] gate weight
+    const float *bias;              // [E] | nullptr
+    int T;
+    int32_t *idx;                   // [T, k] out
+    float *prob;                    // [T, k] out
+    int32_t *row_of, *offsets, *src_row;  // grouping of the routed block, out
+};
 // keep_partials != nullptr: if the launch produces float32 partial sums, leave them in the
 // workspace unreduced and report their number there (0 = y_perm was written directly).
+// gate != nullptr: carry that gate if this launch can (then *gate_done = true), else leave it to the caller.
 int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots, const void *x_perm,
                const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s, int *keep_partials = nullptr,
                const unsigned long long *table = nullptr,  // table: per-expert weight addresses (0 = none), overrides w_base
-               const int32_t *src_row = nullptr);  // bf16 only: x_perm is the un-grouped x [T,d], grouped row r reads x[src_row[r]]
+               const int32_t *src_row = nullptr,  // bf16 only: x_perm is the un-grouped x [T,d], grouped row r reads x[src_row[r]]
+               const FusedGate *gate = nullptr, bool *gate_done = nullptr);
 // p-lanes of the partial-sum reduction for P partials (fixes the order of the additions)
 inline int reduce_lanes(int P) { return P <= 2 ? 1 : (P <= 8 ? 4 : 16); }
 // Combine straight from P unreduced float32 partials [P][n_rows][d] (bf16 contexts only): same

@@ -752,6 +752,9 @@ def test_pull_fetch_with_too_few_slots_flags_and_zeroes(hx, shape):
     # decode-sized batches, where the gate kernel groups the tokens itself: at its limit of 256
     # selections, just beyond it (separate grouping kernel again), and with 256 experts
     ("bf16", 16, 128, 256, 32, 16, 3, False), ("bf16", 16, 128, 256, 32, 17, 3, False), ("bf16", 7, 128, 256, 256, 3, 3, True),
+    # resident store, smallest gates: the decode-sized expert launch of block i carries the pre-gate that routes block
+    # i+1 as an extra workgroup (first two); an expert launch that cannot carry it leaves it to a launch of its own (third)
+    ("bf16", 1, 768, 3072, 8, 1, 4, False), ("bf16", 3, 1024, 4096, 16, 2, 4, False), ("bf16", 4, 128, 256, 8, 2, 3, False),
 ])
 def test_stack_step_equals_the_primitive_call_sequence(hx, dtype, T, d, f, E, k, L, offloaded):
     """pgmoe_stack_step (which fuses the partial-sum reduction into the combine and orders the
@@ -836,6 +839,7 @@ STACK_SHAPES = [
     ("bf16", 5, 64, 64, 256, 8, 4, True, "pull", 3),      # 256 experts, looking three blocks ahead in a four-block stack
     ("bf16", 2, 768, 3072, 8, 2, 2, True, "pull", 0),     # decode kernel with two experts per token
     ("bf16", 4, 1024, 4096, 16, 1, 1, False, "-", 0),     # a single resident block
+    ("bf16", 2, 768, 3072, 8, 2, 3, False, "-", 0),       # resident decode: pre-gates carried by the expert launches
 ]
 
 
