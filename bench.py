@@ -286,7 +286,33 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         out["gpu_only"] = {"value": T * K / dt2, "unit": "tokens/s", "ms_per_step": 1e3 * dt2 / K,
                            "ffn_avg_launch_us": us2, "ffn_achieved_GBps": per_launch / (us2 * 1e-6) / 1e9,
                            "ffn_frac_of_hbm_peak": per_launch / (us2 * 1e-6) / 1e9 / HBM_PEAK_GBPS,
-                           "note": "same workload and routing with all experts resident in HBM (no migration)"}
+                           "note": "same workload and routing with all experts resident in HBM (no migration); a "
+                                   "decode-sized expert launch here also carries the next block's pre-gate as one extra "
+                                   "workgroup, so its duration is that of the combined launch"}
+        if w.dtype == "bf16":
+            # The expert-FFN kernel on its own: the primitive calls (pgmoe_permute, pgmoe_expert_ffn) over
+            # the K steps' routings, block after block, so that every launch reads other experts than the
+            # one before it (the same expert launched back to back is served by the 256 MB last-level
+            # cache, not by HBM); no migration beside it, no pre-gate on board.
+            ctx2 = stack2.ctx
+            ctx2.ffn_timing_begin(K * L)
+            for s_ in range(K):
+                for b in range(L):
+                    ctx2.permute(x_all[s_ % n_in, b], idx_log[s_, b], T, stack2.x_perm, stack2.row_of[b], stack2.expert_offsets[b],
+                                 stack2.compute)
+                    ctx2.expert_ffn(b, stack2.x_perm, stack2.expert_offsets[b], T * k, stack2.y_perm, stack2.workspace,
+                                    stack2.compute)
+            torch.cuda.synchronize()
+            n3, ms3, oh3 = ctx2.ffn_timing_end()
+            us3 = max(1e3 * ms3 / max(n3, 1) - oh3, 1e-3)
+            alone = {"avg_launch_us": us3, "achieved_GBps": per_launch / (us3 * 1e-6) / 1e9,
+                     "frac_of_hbm_peak": per_launch / (us3 * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                     "note": "pgmoe_permute + pgmoe_expert_ffn over the same routings with resident experts, one block after "
+                             "the other: the kernel with no migration beside it and no pre-gate on board"}
+            if ctx2.ffn_kernel_name(T * k).startswith("ffn_gemm"):
+                alone["achieved_TFLOPs"] = 4.0 * T * k * w.d_model * w.d_ff / (us3 * 1e-6) / 1e12
+                alone["frac_of_mfma_peak"] = alone["achieved_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
+            out["roofline"]["kernel_alone"] = alone
         if graphs:
             out["gpu_only"]["graph_replay"] = graph_replay(stack2, bufs2[0], x_all[0, 0])
         stack2.close()
