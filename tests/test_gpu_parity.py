@@ -581,14 +581,18 @@ def test_pregate_distance_routes_from_the_earlier_state_and_keeps_more_generatio
     stack.close()
 
 
-@pytest.mark.parametrize("offloaded", [False, True])
-def test_stack_step_replays_from_a_captured_graph(hx, offloaded):
+@pytest.mark.parametrize("offloaded,shape", [(False, "small"), (True, "small"), (False, "decode"), (True, "decode")])
+def test_stack_step_replays_from_a_captured_graph(hx, offloaded, shape):
     """pgmoe_stack_step only enqueues (pull-mode migration, no host wait, no memset), so a caller
     can capture one step into a HIP graph and replay it: every replay, with the program's own
     eager work and synchronisations in between, must give exactly what the eager step gives."""
     H, B = hx
-    w = small_workload("bf16", 6, 128, 256, 8, 2, L=4, offloaded=offloaded, index=53)
-    say(f"graph replay: offloaded={offloaded}")
+    if shape == "small":
+        w = small_workload("bf16", 6, 128, 256, 8, 2, L=4, offloaded=offloaded, index=53)
+    else:   # batch-size-2 decode of the 8-expert shape: smallest-gate kernel, decode expert kernel (which carries the
+        # next pre-gate when the experts are resident), turn-taking migrations with block 0's on the compute stream
+        w = small_workload("bf16", 2, 768, 3072, 8, 1, L=4, offloaded=offloaded, index=64)
+    say(f"graph replay: offloaded={offloaded} shape={shape}")
     stack, gates, cache = make_stack(H, w, weight_scale=4.0)
     xs_in = [H.to_device(W.step_input(w, s), w.dtype) for s in range(4)]
     eager = []
