@@ -257,7 +257,12 @@ int pgmoe_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, con
  * context owns, and their kernels take turns on the host link in block order (a device-side
  * wait that orders link traffic only, bounded by the clock: no result depends on it); with
  * pregate_distance 1 block 0's (exposed) migration runs on compute_stream itself and block 1's
- * pre-gate runs on the context's stream beside it.
+ * pre-gate runs on the context's stream beside it.  All of this overlaps only if compute_stream,
+ * copy_stream and the context's stream sit on different hardware queues: ask
+ * pgmoe_check_streams() once at set-up.
+ * With a resident store and pregate_distance 1, a decode-sized expert launch (up to 4 tokens, 8
+ * or 16 experts) carries the pre-gate evaluated on the same hidden state as one extra workgroup:
+ * results are those of the separate gate launch, bit for bit.
  * With pregate_distance N > 1 the gate that routes block g is evaluated on x_{max(0, g-N)}:
  * block 0 runs the gates of blocks 0..N on x_0 and queues their fetches back to back, block
  * i >= 1 runs the gate of block i+N; the last N blocks run none.  Arrays of pointers are host arrays of
