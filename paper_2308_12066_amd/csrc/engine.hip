@@ -422,15 +422,20 @@ static int launch_standin(pgmoe_ctx *ctx, void *stream) {
 // on each, started together: side by side they take about `us`, on a shared hardware queue 2 * us.
 static int streams_run_side_by_side(pgmoe_ctx *ctx, hipStream_t a, hipStream_t b, float us, bool *yes) {
     const unsigned long long ticks = (unsigned long long)(us * 100.f);
-    PG_HIP(ctx, hipDeviceSynchronize());
-    const auto t0 = std::chrono::steady_clock::now();
-    hipLaunchKernelGGL(nonmoe_standin_kernel, dim3(1), dim3(64), 0, a, ticks, ticks * 10ull + 1000ull);
-    hipLaunchKernelGGL(nonmoe_standin_kernel, dim3(1), dim3(64), 0, b, ticks, ticks * 10ull + 1000ull);
-    PG_HIP(ctx, hipGetLastError());
-    PG_HIP(ctx, hipStreamSynchronize(a));
-    PG_HIP(ctx, hipStreamSynchronize(b));
-    const float took = std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - t0).count();
-    *yes = took < 1.6f * us;
+    *yes = false;
+    // a second trial if the first one says no: a host thread that loses the CPU between the two
+    // launches looks like a shared queue
+    for (int trial = 0; trial < 2 && !*yes; ++trial) {
+        PG_HIP(ctx, hipDeviceSynchronize());
+        const auto t0 = std::chrono::steady_clock::now();
+        hipLaunchKernelGGL(nonmoe_standin_kernel, dim3(1), dim3(64), 0, a, ticks, ticks * 10ull + 1000ull);
+        hipLaunchKernelGGL(nonmoe_standin_kernel, dim3(1), dim3(64), 0, b, ticks, ticks * 10ull + 1000ull);
+        PG_HIP(ctx, hipGetLastError());
+        PG_HIP(ctx, hipStreamSynchronize(a));
+        PG_HIP(ctx, hipStreamSynchronize(b));
+        const float took = std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - t0).count();
+        *yes = took < 1.6f * us;
+    }
     return PGMOE_OK;
 }
 
