@@ -503,23 +503,6 @@ def test_switch_shaped_stacks(hx, name, blocks, steps, sample, fetch):
     stack.close()
 
 
-def test_streams_of_a_stack_run_side_by_side(hx):
-    """The harness asks the library whether its three streams (compute, copy, the context's own
-    copy stream) share a hardware queue and replaces streams until none do; a stream paired with
-    itself is reported as shared."""
-    H, B = hx
-    w = small_workload("bf16", 4, 128, 256, 8, 1, L=2, offloaded=True, index=63)
-    stacks = []
-    for _ in range(5):          # later stacks of a process get other streams, hence other queues
-        stack, gates, cache = make_stack(H, w, threads=2)
-        assert stack.shared_streams == 0, f"stream pairs that share a hardware queue: {stack.shared_streams}"
-        assert stack.ctx.check_streams(stack.compute, stack.copy) == 0
-        stacks.append(stack)
-    assert stacks[0].ctx.check_streams(stacks[0].compute, stacks[0].compute) & B.STREAMS_COMPUTE_COPY
-    for stack in stacks:
-        stack.close()
-
-
 def test_migrations_of_a_step_take_turns_on_the_host_link(hx):
     """Switch-Base-8 decode shape (one 9.4 MB expert per block): the migration kernels of a step
     finish one after the other, a whole copy apart, instead of sharing the link in pairs (the
@@ -945,3 +928,20 @@ def test_expert_cache_changes_the_copies_not_the_results(hx, policy, shape, dist
     assert cached.ctx.device_flags() == 0
     plain.close()
     cached.close()
+
+
+def test_streams_of_a_stack_run_side_by_side(hx):
+    """The harness asks the library whether its three streams (compute, copy, the context's own
+    copy stream) share a hardware queue and replaces streams until none do; a stream paired with
+    itself is reported as shared."""
+    H, B = hx
+    w = small_workload("bf16", 4, 128, 256, 8, 1, L=2, offloaded=True, index=63)
+    stacks = []
+    for _ in range(5):          # later stacks of a process get other streams, hence other queues
+        stack, gates, cache = make_stack(H, w, threads=2)
+        assert stack.shared_streams == 0, f"stream pairs that share a hardware queue: {stack.shared_streams}"
+        assert stack.ctx.check_streams(stack.compute, stack.copy) == 0
+        stacks.append(stack)
+    assert stacks[0].ctx.check_streams(stacks[0].compute, stacks[0].compute) & B.STREAMS_COMPUTE_COPY
+    for stack in stacks:
+        stack.close()
