@@ -4,6 +4,8 @@
 #include <algorithm>
 #include <new>
 
+#include <cstdlib>
+
 #include "pgmoe_internal.h"
 
 namespace pgmoe {
@@ -21,6 +23,13 @@ int fail(pgmoe_ctx *ctx, int code, const char *fmt, ...) {
 
 int hip_fail(pgmoe_ctx *ctx, hipError_t e, const char *what) {
     return fail(ctx, PGMOE_EHIP, "%s failed: %s", what, hipGetErrorString(e));
+}
+
+const DiagSwitches &diag() {
+    static const DiagSwitches d = {getenv("PGMOE_FFN_NO_DECODE") != nullptr, getenv("PGMOE_FFN_NO_GEMM") != nullptr,
+                                   getenv("PGMOE_FFN_NO_GATE") != nullptr,   getenv("PGMOE_GATE_NO_SMALL") != nullptr,
+                                   getenv("PGMOE_GATE_NO_MFMA") != nullptr,  getenv("PGMOE_GATE_NO_ROUTE") != nullptr};
+    return d;
 }
 
 static int default_slots(const pgmoe_config &c) {

@@ -328,7 +328,7 @@ __global__ __launch_bounds__(256) void ffn_gemm_down_kernel(
 // of LDS many times: at least 192 rows per expert on average.
 constexpr int GEMM_SPLIT = 4;  // most K slices of the down-projection (float32 partials)
 bool uses_gemm_kernels(const pgmoe_config &c, int n_rows) {
-    if (c.dtype != PGMOE_BF16 || getenv("PGMOE_FFN_NO_GEMM")) return false;
+    if (c.dtype != PGMOE_BF16 || diag().ffn_no_gemm) return false;
     // the up kernel's k loop runs in whole rings of 64-k stages, the down kernel's two 32-k tiles per turn in every K slice
     if (c.d_model % GEMM_COLS || c.d_ff % GEMM_COLS || c.d_model % (GEMM_KSTEP * GEMM_RING) || c.d_ff % (GEMM_SPLIT * 64)) return false;
     const int active = std::max(1, std::min(c.n_experts, n_rows));
