@@ -516,11 +516,7 @@ static int launch_fused(pgmoe_ctx *ctx, const FfnPlan &p, const char *w_base, si
     const pgmoe_config &c = ctx->cfg;
     const size_t lds = (size_t)MT * KT * 1024 + 2u * MT * (16 * NW / 32) * 1024;
     auto kern = ffn_fused_kernel<MT, KT, NW, D>;
-    static thread_local bool attr_set = false;  // per instantiation
-    if (lds > 48 * 1024 && !attr_set) {
-        PG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
+    if (int rc = allow_dynamic_lds(ctx, reinterpret_cast<const void *>(kern), lds)) return rc;
     float *partial = p.n_partial > 1 ? (float *)workspace : nullptr;
     if (partial && (size_t)p.n_partial * n_rows * c.d_model * 4 > ffn_workspace_bytes(c))
         return fail(ctx, PGMOE_EINVAL, "pgmoe_expert_ffn: %d partial sums of %d rows do not fit the workspace", p.n_partial, n_rows);

@@ -371,12 +371,7 @@ int launch_ffn_gemm(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool sl
 #define PG_DOWN(NS_)                                                                                                             \
 do {                                                                                                                         \
     constexpr int lds = NS_ * 2 * (GEMM_ROWS / 16) * 1024;                                                                   \
-    static thread_local bool attr_set = false;                                                                               \
-    if (!attr_set) {                                                                                                         \
-        PG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(ffn_gemm_down_kernel<NS_>),                           \
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds));                                   \
-        attr_set = true;                                                                                                     \
-    }                                                                                                                        \
+    if (int rc_ = allow_dynamic_lds(ctx, reinterpret_cast<const void *>(ffn_gemm_down_kernel<NS_>), lds)) return rc_;       \
     hipLaunchKernelGGL(ffn_gemm_down_kernel<NS_>, grid_down, dim3(256), lds, s, (const char *)h, offsets, c.n_experts,       \
                        c.d_model, c.d_ff, split, w_base, w_stride, slot_by_rank ? 1 : 0, n_slots, table, partial, n_rows);   \
 } while (0)

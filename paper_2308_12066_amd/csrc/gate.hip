@@ -315,11 +315,7 @@ static int launch_gate_mfma(pgmoe_ctx *ctx, const __bf16 *x, const __bf16 *w, co
     do {                                                                                                                \
         auto kern = gate_topk_mfma_kernel<NP_, NW_>;                                                                    \
         const size_t lds = (size_t)(NW_ + 1) * GM_TOK * NP_ * 128 * sizeof(float); /* NW partial planes + the logits */ \
-        static thread_local bool attr_set = false;                                                                      \
-        if (lds > 48 * 1024 && !attr_set) {                                                                             \
-            PG_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
-            attr_set = true;                                                                                            \
-        }                                                                                                               \
+        if (int rc_ = allow_dynamic_lds(ctx, reinterpret_cast<const void *>(kern), lds)) return rc_;                    \
         hipLaunchKernelGGL(kern, grid, dim3(NW_ * 64), lds, s, x, w, bias, T, c.d_model, c.n_experts, c.top_k, idx, prob, probs, \
                            ctx->dev_flags, row_of, offsets, src_row);                                                   \
     } while (0)

@@ -101,6 +101,10 @@ struct pgmoe_ctx {
     bool tim_on;
     float tim_overhead_ms;  // what one event pair adds around a kernel
 
+    // kernels whose dynamic-LDS limit has been raised for this context's device (allow_dynamic_lds)
+    const void *lds_ready[48] = {};
+    int n_lds_ready = 0;
+
     char err[512];
 };
 
@@ -131,6 +135,17 @@ int check_config(const pgmoe_config *cfg, char *buf, size_t n);
     } while (0)
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// A launch with more than 48 KiB of dynamic LDS needs the kernel's limit raised first, once per
+// kernel and device; the context remembers which of its kernels have had that done.
+inline int allow_dynamic_lds(pgmoe_ctx *ctx, const void *kernel, size_t bytes) {
+    if (bytes <= 48 * 1024) return PGMOE_OK;
+    for (int i = 0; i < ctx->n_lds_ready; ++i)
+        if (ctx->lds_ready[i] == kernel) return PGMOE_OK;
+    PG_HIP(ctx, hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    if (ctx->n_lds_ready < (int)(sizeof ctx->lds_ready / sizeof ctx->lds_ready[0])) ctx->lds_ready[ctx->n_lds_ready++] = kernel;
+    return PGMOE_OK;
+}
 
 // Geometry of the bf16 FFN launch for n_rows permuted rows (host side, deterministic):
 // rows per workgroup chunk, number of d_ff ranges (partial sums) and the chunk-count bound.
