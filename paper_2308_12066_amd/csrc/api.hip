@@ -83,14 +83,8 @@ int check_config(const pgmoe_config *c, char *buf, size_t n) {
 }  // namespace pgmoe
 
 // ---------------------------------------------------------------- weight layout (host)
-// Position of element (k, n) of a [K, N] bf16 matrix in the tiled layout described in pgmoe.h.
-static inline size_t tiled_pos(int k, int n, int K, int N, bool nt_major) {
-    const int kt = k >> 5, nt = n >> 4;
-    const size_t tile = nt_major ? (size_t)nt * (K >> 5) + kt : (size_t)kt * (N >> 4) + nt;
-    const int lane = (n & 15) + 16 * ((k & 31) >> 3);
-    return tile * 512 + (size_t)lane * 8 + (k & 7);
-}
-
+// Element (k, n) of a [K, N] bf16 matrix sits in tile (k/32, n/16) at ((n%16) + 16*((k%32)/8))*8 + k%8
+// (the layout described in pgmoe.h); tiles are ordered n-major or k-major.
 template <bool PACK>
 static void tile_copy(uint16_t *tiled, uint16_t *plain, int K, int N, bool nt_major) {
     for (int kt = 0; kt < K / 32; ++kt)
