@@ -16,8 +16,7 @@ Nothing here imports or calls the HIP library.
 from __future__ import annotations
 
 import ctypes
-import os
-from typing import Callable, Optional, Sequence
+from typing import Callable, Sequence
 
 import numpy as np
 

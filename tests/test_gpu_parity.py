@@ -3,7 +3,6 @@ on the same seeded inputs.  Integer results (expert indices away from near-ties,
 row_of, permuted rows) must be bit-exact; floating point within the stated tolerances:
 normalised max-abs error 1e-5 (f32) and 2e-2 (bf16).
 """
-import os
 import sys
 
 import numpy as np
