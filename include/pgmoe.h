@@ -255,9 +255,9 @@ int pgmoe_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, con
  * bookkeeping alternates between two device copies from call to call).
  * In pull mode the migrations of one call alternate between copy_stream and a second stream the
  * context owns, and their kernels take turns on the host link in block order (a device-side
- * wait that orders link traffic only, bounded by the clock: no result depends on it); with
- * pregate_distance 1 block 0's (exposed) migration runs on compute_stream itself and block 1's
- * pre-gate runs on the context's stream beside it.  All of this overlaps only if compute_stream,
+ * wait that orders link traffic only, bounded by the clock: no result depends on it); block 0's
+ * (exposed) migration runs on compute_stream itself and block 1's pre-gate runs on the
+ * context's stream beside it (bf16 contexts).  All of this overlaps only if compute_stream,
  * copy_stream and the context's stream sit on different hardware queues: ask
  * pgmoe_check_streams() once at set-up.
  * With a resident store and pregate_distance 1, a decode-sized expert launch (up to 4 tokens, 8

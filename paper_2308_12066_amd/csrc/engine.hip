@@ -620,7 +620,7 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
     // it is a decode-sized launch with one of the smallest gates (one launch fewer per block);
     // a launch that cannot leaves it to a gate launch of its own right behind it.
     const bool carry_gate = ctx->store_mode == STORE_RESIDENT && N == 1 && c.dtype == PGMOE_BF16;
-    if (ctx->pull_seq >= 0 && N == 1 && c.dtype == PGMOE_BF16) {
+    if (ctx->pull_seq >= 0 && c.dtype == PGMOE_BF16) {
         // Block 0's fetch is exposed whatever is done, so it runs on the compute stream itself,
         // right behind its gate: no stream hand-over (11-13 us) before the link starts working,
         // and none before block 0's experts either.  Block 1's pre-gate and fetch go to the
@@ -642,6 +642,15 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
             ctx->routed_on_copy_stream = true;  // turn 1 is odd: the fetch goes to the same stream
             rc = pgmoe_fetch_experts(ctx, 1, idx_at(1), T, compute_stream, copy_stream, nullptr);
             ctx->routed_on_copy_stream = false;
+            if (rc) return rc;
+        }
+        // blocks 2..N (pre-gate distance N > 1) are routed from x_0 as well; their gates queue on the
+        // compute stream behind block 0's migration, early enough: their turn on the link comes
+        // only after blocks 0 and 1 have been copied
+        for (int g = 2; g <= head; ++g) {
+            rc = gate_for_block(ctx, io, g, x_at(0), T, compute_stream);
+            if (rc) return rc;
+            rc = pgmoe_fetch_experts(ctx, g, idx_at(g), T, compute_stream, copy_stream, nullptr);
             if (rc) return rc;
         }
     } else {
