@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the pre-gated MoE hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--also cfg3,cfg4] [--all]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--also cfg5_top2,cfg2,...] [--all]
 
 A "step" is one pass of the whole hot path over one batch: conventional gate of block 0,
 pre-gates, migration of the pre-gated experts from pinned host memory, token grouping,
@@ -9,9 +9,10 @@ expert FFNs and weighted combine, for all L blocks of the stack.  Inputs (hidden
 every step, gate weights) are resident in HBM before the timed region; the expert store is in
 pinned host memory (offloaded workloads) or in HBM (resident workloads), as the workload says.
 
-Prints ONE JSON line.  The headline numbers are those of --workload (default: the
-Switch-Base-8 decode stack); --also adds abbreviated results of other workloads under
-"other_workloads" (same measurement, fewer steps).
+Prints ONE JSON line.  The headline numbers are those of --workload (default: the largest
+configuration, the Switch-Large-128 decode stack with top-1 routing, 25.8 GB of experts in pinned
+host memory); --also adds abbreviated results of other workloads under "other_workloads" (same
+measurement, fewer steps); the top-2 run of the same model shares the headline's expert store.
 """
 from __future__ import annotations
 
@@ -35,32 +36,66 @@ def log(msg):
     print(msg, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(w, steps_sample):
-    """Time the CPU oracle (as it stands) on a bounded sample of the same workload."""
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(w, steps_sample, host_threads):
+    """Time the CPU oracle (as it stands) on a bounded sample of the same workload: once on one
+    thread and once on all the threads OpenMP gives it here (it parallelises over tokens, so it can
+    use at most T of them)."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    import numpy as np
+
     import workloads as W
     from oracle import reference as R
 
     gates = W.gate_tensors(w)
     cache = {}
 
-    def get(b, e):
-        if (b, e) not in cache:
-            w1, w2 = W.expert_weights(w, b, e)
-            cache[(b, e)] = (W.to_bf16_bits(w1), W.to_bf16_bits(w2)) if w.dtype == "bf16" else (w1, w2)
-        return cache[(b, e)]
+    def gen(be):
+        if be not in cache:
+            w1, w2 = W.expert_weights(w, *be)
+            cache[be] = (W.to_bf16_bits(w1), W.to_bf16_bits(w2)) if w.dtype == "bf16" else (w1, w2)
 
     xs = [W.step_input(w, s) for s in range(steps_sample)]
-    for x in xs:                                    # untimed pass: generates the experts the routing needs
-        R.stack_forward(x, gates, w.top_k, get, w.d_ff)
-    t0 = time.perf_counter()
-    for x in xs:
-        R.stack_forward(x, gates, w.top_k, get, w.d_ff)
-    dt = time.perf_counter() - t0
-    threads = min(R.max_threads(), w.tokens)        # the oracle parallelises over tokens only
-    return {"value": w.tokens * steps_sample / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{steps_sample} steps x {w.n_blocks} blocks x {w.tokens} tokens of {w.name} (fp64, routed), "
-                      f"{dt:.2f} s; expert weight generation excluded",
-            "ms_per_token_per_layer": 1e3 * dt / (w.tokens * steps_sample * w.n_blocks)}
+    # untimed pass: the same chain block by block, generating the experts each block's routing asks
+    # for on a thread pool (weight generation is not part of what is timed)
+    with ThreadPoolExecutor(max_workers=max(1, host_threads)) as pool:
+        for x0 in xs:
+            hs = [np.asarray(x0, np.float64)]
+            for i, (gw, gb) in enumerate(gates):
+                g = R.gate(hs[R.routing_source(i)], gw, gb, w.top_k)
+                need = [(i, int(e)) for e in np.unique(g["idx"])]
+                list(pool.map(gen, need))
+                y = R.block(hs[i], g["p"], g["idx"], {e: cache[(b, e)] for b, e in need}, w.d_ff)
+                hs.append(hs[i] + y)
+
+    def timed(threads):
+        t0 = time.perf_counter()
+        for x in xs:
+            R.stack_forward(x, gates, w.top_k, lambda b, e: cache[(b, e)], w.d_ff, threads=threads)
+        return time.perf_counter() - t0
+
+    n_all = int(min(R.max_threads(), w.tokens))
+    dt1 = timed(1)
+    dtn = timed(n_all) if n_all > 1 else dt1
+    tok = w.tokens * steps_sample
+    return {"value": tok / dtn, "unit": "tokens/s", "cores": n_all, "kind": "oracle",
+            "sample": f"{steps_sample} steps x {w.n_blocks} blocks x {w.tokens} tokens of {w.name} (fp64, routed): "
+                      f"{dtn:.2f} s on {n_all} threads, {dt1:.2f} s on one; expert weight generation excluded",
+            "ms_per_token_per_layer": 1e3 * dtn / (tok * w.n_blocks),
+            "single_thread": {"value": tok / dt1, "unit": "tokens/s", "cores": 1,
+                              "ms_per_token_per_layer": 1e3 * dt1 / (tok * w.n_blocks)},
+            "host": {"cpu_model": cpu_model(), "threads_openmp_offers": int(R.max_threads()),
+                     "logical_cpus": os.cpu_count()}}
 
 
 def measured_peaks():
@@ -101,7 +136,7 @@ def pmc_traffic(workload_name):
 
 
 def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gpu_only=True, systems=False,
-                 cache_frac=0.2, store=None, graphs=False):
+                 cache_frac=0.2, store=None, graphs=False, fetch_mode="pull"):
     import numpy as np
     import torch
 
@@ -118,7 +153,8 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
     own_store = store is None
     if own_store:
         store = H.ExpertStore(w, cfg, threads=host_threads)
-    stack = H.Stack(w, store)
+    from paper_2308_12066_amd import binding as B
+    stack = H.Stack(w, store, flags=B.FLAG_FETCH_MEMCPY if fetch_mode == "memcpy" else 0)
     # Every timed step gets its own hidden-state block (slice 0 pre-filled with that step's
     # input) and its own routing-index slice, so the timed loop holds library calls only.
     n_in = min(K, max(1, (1 << 30) // ((L + 1) * T * w.d_model * w.elem_bytes)))   # distinct inputs kept in HBM
@@ -210,7 +246,9 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         "data": "synthetic",
         "config": {"workload": f"{w.name}: L={L} d_model={w.d_model} d_ff={w.d_ff} E={E} top{k} T={T}/step, "
                                f"experts {'offloaded to pinned host memory' if w.offloaded else 'resident in HBM'}",
-                   "tokens_per_step": T, "blocks": L},
+                   "tokens_per_step": T, "blocks": L,
+                   "migration": ("hipMemcpyAsync per expert, issued by the host" if fetch_mode == "memcpy" else
+                                 "device-side pull kernel") if w.offloaded else "none"},
         "ms_per_token": 1e3 * dt / (T * K),
         "ms_per_token_per_layer": 1e3 * dt / (T * K * L),
         "block_latency_us": 1e6 * dt / (K * L),
@@ -236,7 +274,7 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         out["roofline"].update({"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                 "frac": tf / MFMA_BF16_PEAK_TFLOPS, "flops_per_launch": flops,
                                 "hbm_achieved_GBps": ffn_gbps, "hbm_frac": ffn_gbps / HBM_PEAK_GBPS})
-    if graphs:
+    if graphs and not (w.offloaded and fetch_mode == "memcpy"):   # the host-issued migration cannot be captured
         out["graph_replay"] = graph_replay(stack, step_bufs[0], x_all[0, 0])
     if w.offloaded and trace_steps > 0:
         # pass 3: instrumented steps for the overlap figures (per-block events on both streams)
@@ -317,11 +355,10 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
             out["gpu_only"]["graph_replay"] = graph_replay(stack2, bufs2[0], x_all[0, 0])
         stack2.close()
         del stack2, bufs2
-    if w.offloaded and cache_frac > 0:
+    if w.offloaded and cache_frac > 0 and fetch_mode == "pull":
         # Expert cache on top of the migration (the paper's caching study: a fraction of each
         # block's experts kept in HBM across steps; LRU here, all three policies for the headline
         # workload).  A labelled extra: `value` above is the base design without a cache.
-        from paper_2308_12066_amd import binding as B
         C = max(1, min(B.MAX_CACHE_SLOTS, int(np.ceil(cache_frac * E))))
         out["expert_cache"] = {"slots_per_block": C, "fraction_of_experts": C / E}
         pols = (("lru", B.CACHE_LRU), ("lfu", B.CACHE_LFU), ("lifo", B.CACHE_LIFO)) if systems else (("lru", B.CACHE_LRU),)
@@ -355,7 +392,6 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         # The paper's comparison systems on the same kernels and the same workload (conventional
         # wiring): experts fetched on demand after the gate, or all experts of the next block
         # prefetched.  Block latency is what the paper's latency figure compares.
-        from paper_2308_12066_amd import binding as B
         Ks = min(K, 32)
         comp = {"pregated": {"block_latency_us": 1e6 * dt / (K * L), "tokens_per_s": T * K / dt,
                              "peak_resident_expert_MB": float((uniq[:, :-1] + uniq[:, 1:]).max() if L > 1 else uniq.max())
@@ -419,13 +455,16 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         # block.  Shows where the design's benefit comes from: once the work per block reaches the
         # migration time, the migration of every block but the first disappears behind it.
         sens = {}
-        Kq = min(K, 32)
+        Kq = min(K, 32 if 1e3 * dt / K < 5.0 else 8)
         # one Stack for every row: the same streams, hence the same hardware queues, throughout
         stk = H.Stack(w, store)
         bufs = [stk.ctx.make_step_buffers(stk.gate_w, stk.gate_b, x_all[s % n_in], stk.y_blocks, idx_log[s],
                                           stk.topk_prob, stk.row_of, stk.expert_offsets, stk.x_perm, stk.y_perm,
                                           stk.workspace) for s in range(Kq)]
-        for us in (0.0, 100.0, 200.0, 400.0):
+        # stand-in durations: none, then about 0.6, 1.2 and 2.4 times this workload's block latency
+        # (100 / 200 / 400 us for the batch-1 decode stack, whose block takes 170 us)
+        unit_us = max(100.0, 100.0 * round(0.6 * 1e6 * dt / (K * L) / 100.0))
+        for us in (0.0, unit_us, 2.0 * unit_us, 4.0 * unit_us):
             row = {}
             for sname, sched in (("pregated", B.SCHED_PREGATED), ("on_demand", B.SCHED_ON_DEMAND)):
                 stk.ctx.set_schedule(sched)
@@ -465,11 +504,15 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
                     "non-MoE layers of the real model; block latency includes it",
             "by_standin_us": sens}
     if with_cpu:
-        # about 10 s of oracle time (12.6 ms per batch-1 step of the six-block stack on one core)
-        sample = cpu_steps or max(1, min(1000, int(round(4800.0 / (T * L * k)))))
+        # about 10 s of oracle time on one thread (2.1 ms per token and block at d_model 768, d_ff 3072,
+        # in proportion to d_model * d_ff elsewhere), then the same steps on all threads
+        per_step_s = 2.1e-3 * T * L * k * (w.d_model * w.d_ff) / (768.0 * 3072.0)
+        sample = cpu_steps or max(1, min(1000, int(round(10.0 / per_step_s))))
         log(f"[bench] {w.name}: timing the CPU oracle on {sample} steps")
-        out["cpu_baseline"] = cpu_baseline(w, sample)
+        out["cpu_baseline"] = cpu_baseline(w, sample, host_threads)
     stack.close()
+    if own_store:
+        store.device = None
     del stack, store, x_all, step_bufs
     torch.cuda.empty_cache()
     return out
@@ -506,11 +549,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="cfg2")
-    ap.add_argument("--also", default="cfg3,cfg4,base8_prefill",
+    ap.add_argument("--workload", default="cfg5")
+    ap.add_argument("--also", default="cfg5_top2,cfg2,cfg3,cfg4,base8_prefill",
                     help="comma list of further workloads to summarise ('' for none); base8_prefill is the supplementary "
                          "shape with ~512 rows per expert, where the FFN is bound by the matrix cores")
-    ap.add_argument("--all", action="store_true", help="also run the offloaded Switch-Base-128 and both Switch-Large-128 runs")
+    ap.add_argument("--all", action="store_true", help="also run the offloaded Switch-Base-128 prefill")
+    ap.add_argument("--fetch", default="pull", choices=("pull", "memcpy"),
+                    help="migration engine of the offloaded workloads: the device-side pull kernel (default) or one "
+                         "hipMemcpyAsync per expert issued by the host")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-steps", type=int, default=None)
     ap.add_argument("--trace-steps", type=int, default=8)
@@ -526,23 +572,55 @@ def main():
         sys.exit(2)
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    import workloads as W
+    from paper_2308_12066_amd import harness as H
 
-    if args.main_only:
-        out = run_workload(args.workload, args.steps, args.warmup, args.host_threads, not args.no_cpu_baseline,
-                           args.cpu_sample_steps, args.trace_steps, gpu_only=False, systems=False, cache_frac=0.0)
-    else:
-        out = run_workload(args.workload, args.steps, args.warmup, args.host_threads, not args.no_cpu_baseline,
-                           args.cpu_sample_steps, args.trace_steps, systems=True, graphs=True)
-    out["measured_peaks"] = measured_peaks()
     others = [n for n in args.also.split(",") if n and n != args.workload]
     if args.all:
-        others += [n for n in ("cfg4_offloaded", "cfg5", "cfg5_top2") if n not in others]
-    short = {"cfg1": 8, "cfg3": 24, "cfg4": 4, "cfg4_offloaded": 2, "cfg5": 6, "cfg5_top2": 6, "base8_prefill": 4}
+        others += [n for n in ("cfg4_offloaded",) if n not in others]
+    # workloads with the same seed index have the same expert weights (Switch-Large-128 top-1 and
+    # top-2; the resident and the offloaded prefill): they share one expert store
+    stores = {}
+
+    def store_for(name):
+        w = W.CONFIGS[name]
+        users = [n for n in [args.workload] + others if W.CONFIGS[n].index == w.index]
+        if len(users) < 2:
+            return None
+        if w.index not in stores:
+            t0 = time.perf_counter()
+            stores[w.index] = H.ExpertStore(w, H.config_for(w), threads=args.host_threads)
+            log(f"[bench] shared expert store of {', '.join(users)}: built in {time.perf_counter() - t0:.1f} s")
+        return stores[w.index]
+
+    def drop_store(name):
+        """The last user of a shared store has run: give its pinned and device memory back."""
+        w = W.CONFIGS[name]
+        rest = [n for n in pending if W.CONFIGS[n].index == w.index]
+        if not rest and w.index in stores:
+            stores.pop(w.index).device = None
+            torch.cuda.empty_cache()
+
+    pending = list(others)
+    if args.main_only:
+        out = run_workload(args.workload, args.steps, args.warmup, args.host_threads, not args.no_cpu_baseline,
+                           args.cpu_sample_steps, args.trace_steps, gpu_only=False, systems=False, cache_frac=0.0,
+                           store=store_for(args.workload), fetch_mode=args.fetch)
+    else:
+        out = run_workload(args.workload, args.steps, args.warmup, args.host_threads, not args.no_cpu_baseline,
+                           args.cpu_sample_steps, args.trace_steps, systems=True, graphs=True, store=store_for(args.workload),
+                           fetch_mode=args.fetch)
+    drop_store(args.workload)
+    out["measured_peaks"] = measured_peaks()
+    short = {"cfg1": 8, "cfg2": 32, "cfg3": 24, "cfg4": 4, "cfg4_offloaded": 2, "cfg5": 6, "cfg5_top2": 6, "base8_prefill": 4}
     keep = ("value", "unit", "steps", "ms_per_step", "ms_per_token_per_layer", "block_latency_us", "config", "roofline",
             "host_link", "overlap", "gpu_only", "expert_cache")
     out["other_workloads"] = {}
     for n in others:
-        r = run_workload(n, short.get(n, 8), 2, args.host_threads, False, None, min(args.trace_steps, 2))
+        pending.remove(n)
+        r = run_workload(n, short.get(n, 8), 2, args.host_threads, False, None, min(args.trace_steps, 2), store=store_for(n),
+                         fetch_mode=args.fetch)
+        drop_store(n)
         out["other_workloads"][n] = {k: r[k] for k in keep if k in r}
     if args.sweep_k:
         out["activated_expert_sweep"] = activated_expert_sweep(args.host_threads, 16)

@@ -21,7 +21,12 @@
  *     "pinned" host memory obtained from hipHostMalloc.  The caller owns every buffer it
  *     passes and keeps it alive until the stream work that uses it has completed.  The
  *     library owns only the context: the expert slot pool, events and a small pinned
- *     staging area.  No call allocates memory after pgmoe_create().
+ *     staging area.  Allocation happens in set-up calls only: pgmoe_create() (flags, maps,
+ *     events, staging), the first pgmoe_register_host_experts() on a context (slot pool and,
+ *     if configured, the expert cache), pgmoe_check_streams() (may create streams) and
+ *     pgmoe_ffn_timing_begin() (its events).  The calls of the hot path (pgmoe_pregate_topk,
+ *     pgmoe_fetch_experts, pgmoe_permute, pgmoe_expert_ffn, pgmoe_combine, pgmoe_stack_step)
+ *     allocate nothing.
  *   - Streams are hipStream_t passed as void* (NULL = the default stream).  All device work
  *     is asynchronous on the given stream, except that pgmoe_fetch_experts() waits until the
  *     routing indices have reached the host (it must read them to issue the copies).

@@ -4,8 +4,6 @@
 #include <algorithm>
 #include <new>
 
-#include <cstdlib>
-
 #include "pgmoe_internal.h"
 
 namespace pgmoe {
@@ -23,13 +21,6 @@ int fail(pgmoe_ctx *ctx, int code, const char *fmt, ...) {
 
 int hip_fail(pgmoe_ctx *ctx, hipError_t e, const char *what) {
     return fail(ctx, PGMOE_EHIP, "%s failed: %s", what, hipGetErrorString(e));
-}
-
-const DiagSwitches &diag() {
-    static const DiagSwitches d = {getenv("PGMOE_FFN_NO_DECODE") != nullptr, getenv("PGMOE_FFN_NO_GEMM") != nullptr,
-                                   getenv("PGMOE_FFN_NO_GATE") != nullptr,   getenv("PGMOE_GATE_NO_SMALL") != nullptr,
-                                   getenv("PGMOE_GATE_NO_MFMA") != nullptr,  getenv("PGMOE_GATE_NO_ROUTE") != nullptr};
-    return d;
 }
 
 static int default_slots(const pgmoe_config &c) {
@@ -211,7 +202,9 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
         size_t n_idx = (size_t)cfg->max_tokens * cfg->top_k;
         if (rc == PGMOE_OK) H(hipMalloc((void **)&c->dev_src_row, (size_t)cfg->n_blocks * n_idx * sizeof(int32_t)), "hipMalloc(src_row)");
         if (rc == PGMOE_OK) H(hipHostMalloc((void **)&c->idx_staging, n_idx * sizeof(int32_t), hipHostMallocDefault), "hipHostMalloc(idx staging)");
-        if (rc == PGMOE_OK) H(hipEventCreateWithFlags(&c->idx_ready, hipEventDisableTiming | hipEventReleaseToDevice), "hipEventCreate");
+        // idx_ready is the one event the host itself polls before it reads the staged indices (memcpy
+        // mode): it keeps the default, system-scope release, so the copy before it is visible to the host
+        if (rc == PGMOE_OK) H(hipEventCreateWithFlags(&c->idx_ready, hipEventDisableTiming), "hipEventCreate");
         if (rc == PGMOE_OK) H(hipEventCreateWithFlags(&c->step_start, hipEventDisableTiming | hipEventReleaseToDevice), "hipEventCreate");
         if (rc == PGMOE_OK) H(hipStreamCreateWithFlags(&c->copy2, hipStreamNonBlocking), "hipStreamCreate");
         for (int g = 0; g < kGen && rc == PGMOE_OK; ++g) {

@@ -471,7 +471,7 @@ bool ffn_supports_d_model(int d_model) { return d_model % 32 == 0 && fused_case_
 // 32-column sub-slab (what plan_ffn picks when only a few experts are active).
 static bool uses_decode_kernel(const pgmoe_config &c, const FfnPlan &p) {
     const int kt = c.d_model / 32;
-    return p.mt == 1 && p.nw == 2 && p.n_partial == c.d_ff / 32 && (kt == 24 || kt == 32) && !diag().ffn_no_decode;
+    return p.mt == 1 && p.nw == 2 && p.n_partial == c.d_ff / 32 && (kt == 24 || kt == 32);
 }
 
 const char *ffn_kernel_name(const pgmoe_config &c, int n_rows) {
@@ -570,7 +570,7 @@ int launch_ffn(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by
         if (tslot >= 0) PG_HIP(ctx, hipEventRecord(ctx->tim_begin[tslot], s));
         // one more row of workgroups for the pre-gate this launch carries, if it is one the smallest-gate code serves
         DecodeGate dg = {};
-        if (gate && gate_done && gate_small_applies(c, gate->T) && !diag().ffn_no_gate) {
+        if (gate && gate_done && gate_small_applies(c, gate->T)) {
             dg = DecodeGate{(const __bf16 *)gate->x, (const __bf16 *)gate->w, gate->bias, gate->T, c.top_k, c.n_experts, gate->idx,
                             gate->prob, ctx->dev_flags, gate->row_of, gate->offsets, gate->src_row};
             *gate_done = true;

@@ -198,7 +198,7 @@ __device__ inline unsigned lds_address(const void *p) {
     return (unsigned)(size_t)(__attribute__((address_space(3))) const char *)p;
 }
 __device__ inline void load_tile_to_lds(const char *src_lane, unsigned lds_tile) {  // src_lane: this lane's 16 bytes
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src_lane), "s"(lds_tile) : "memory");
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src_lane), "s"(lds_tile) : "memory", "m0");
 }
 
 template <int NS>
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(256) void ffn_gemm_down_kernel(
 // of LDS many times: at least 192 rows per expert on average.
 constexpr int GEMM_SPLIT = 4;  // most K slices of the down-projection (float32 partials)
 bool uses_gemm_kernels(const pgmoe_config &c, int n_rows) {
-    if (c.dtype != PGMOE_BF16 || diag().ffn_no_gemm) return false;
+    if (c.dtype != PGMOE_BF16) return false;
     // the up kernel's k loop runs in whole rings of 64-k stages, the down kernel's two 32-k tiles per turn in every K slice
     if (c.d_model % GEMM_COLS || c.d_ff % GEMM_COLS || c.d_model % (GEMM_KSTEP * GEMM_RING) || c.d_ff % (GEMM_SPLIT * 64)) return false;
     const int active = std::max(1, std::min(c.n_experts, n_rows));

@@ -303,7 +303,7 @@ static int launch_gate_mfma(pgmoe_ctx *ctx, const __bf16 *x, const __bf16 *w, co
     const bool route = row_of && offsets && src_row && grid.x == 1 && T * c.top_k <= GATE_ROUTE_MAX;
     if (!route) row_of = offsets = src_row = nullptr;
     if (routed) *routed = route;
-    if (gate_small_applies(c, T) && !diag().gate_no_small) {
+    if (gate_small_applies(c, T)) {
         hipLaunchKernelGGL(gate_small_kernel, dim3(1), dim3(GS_THREADS), 0, s, c.n_experts, x, w, bias, T, c.d_model, c.top_k, idx,
                            prob, probs, ctx->dev_flags, row_of, offsets, src_row);
         PG_HIP(ctx, hipGetLastError());
@@ -330,9 +330,9 @@ int launch_gate(pgmoe_ctx *ctx, const void *x, const void *w, const float *bias,
                 float *prob, float *probs, hipStream_t s, int32_t *row_of, int32_t *offsets, int32_t *src_row, bool *routed) {
     const pgmoe_config &c = ctx->cfg;
     if (routed) *routed = false;
-    if (c.dtype == PGMOE_BF16 && c.n_experts % 8 == 0 && c.d_model % 32 == 0 && !diag().gate_no_mfma)
+    if (c.dtype == PGMOE_BF16 && c.n_experts % 8 == 0 && c.d_model % 32 == 0)
         return launch_gate_mfma(ctx, (const __bf16 *)x, (const __bf16 *)w, bias, T, idx, prob, probs, s,
-                                diag().gate_no_route ? nullptr : row_of, offsets, src_row, routed);
+                                row_of, offsets, src_row, routed);
     if (c.dtype == PGMOE_F32)
         launch_gate_t<float>(c, (const float *)x, (const float *)w, bias, T, idx, prob, probs, ctx->dev_flags, s);
     else

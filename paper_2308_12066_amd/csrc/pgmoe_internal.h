@@ -110,19 +110,6 @@ struct pgmoe_ctx {
 
 namespace pgmoe {
 
-// Diagnostic switches, read from the environment once per process and used by no test or bench
-// line: each keeps launches off one specialised path so that it can be timed against the general
-// one (results are the same either way).
-struct DiagSwitches {
-    bool ffn_no_decode;   // PGMOE_FFN_NO_DECODE: no decode-sized expert kernel
-    bool ffn_no_gemm;     // PGMOE_FFN_NO_GEMM: no two-GEMM path
-    bool ffn_no_gate;     // PGMOE_FFN_NO_GATE: an expert launch never carries a pre-gate
-    bool gate_no_small;   // PGMOE_GATE_NO_SMALL: no smallest-gate kernel
-    bool gate_no_mfma;    // PGMOE_GATE_NO_MFMA: no matrix-core gate kernel
-    bool gate_no_route;   // PGMOE_GATE_NO_ROUTE: the gate kernel never groups the tokens itself
-};
-const DiagSwitches &diag();
-
 int fail(pgmoe_ctx *ctx, int code, const char *fmt, ...) __attribute__((format(printf, 3, 4)));
 int hip_fail(pgmoe_ctx *ctx, hipError_t e, const char *what);
 // Validates cfg; on failure writes the reason to buf and returns PGMOE_EINVAL.

@@ -381,6 +381,8 @@ def check_stack_step(H, w, stack, gates, expert_cache, sample_tokens=None, label
         if sample_tokens is not None and len(toks) > sample_tokens:
             toks = np.sort(np.random.default_rng(i).choice(toks, sample_tokens, replace=False))
         need = np.unique(o["idx"][toks])
+        if hasattr(expert_cache, "prefetch"):      # a source that generates a block's experts in parallel
+            expert_cache.prefetch(i, need)
         experts = {int(e): expert_cache(i, int(e)) for e in need}
         y_ref = R.block(xs[i][toks], o["p"][toks], o["idx"][toks], experts, w.d_ff)
         err = nerr(ys[i][toks], y_ref)
