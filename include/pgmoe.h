@@ -234,6 +234,26 @@ int pgmoe_permute(pgmoe_ctx *ctx, const void *x, const int32_t *topk_idx, int T,
 int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_t *expert_offsets,
                      int n_rows, void *y_perm, void *workspace, void *stream);
 
+/* ---- for callers that cannot allocate ----------------------------------------------------
+ * pgmoe_expert_ffn() for code under HIP graph capture, tight serving loops and harnesses that
+ * forbid hipMalloc: same operation, same results bit for bit, but the float32 partial sums (for
+ * launches with hundreds of rows per expert also the packed hidden activation) go to a buffer
+ * of PGMOE_STATIC_SCRATCH_BYTES that is part of the library's device image instead of a
+ * workspace the caller had to allocate.  Every GPU the library runs on holds one such buffer
+ * from the moment the library is loaded there until the process ends.  The call allocates
+ * nothing (no hipMalloc / hipFree, no allocating library routine) and otherwise behaves as
+ * pgmoe_expert_ffn() (same arguments without `workspace`, same waits and events).
+ *   - A launch that needs more scratch than the buffer holds is refused with PGMOE_EINVAL and a
+ *     text that names both sizes (decode-sized launches need a few MiB; 4096 rows over 128
+ *     experts would need 201 MB: use pgmoe_expert_ffn with a workspace there).
+ *   - All calls on one GPU, from every context, share the buffer and it keeps the last call's
+ *     contents: nothing in it has to start at zero (every partial sum that is read was written
+ *     by the same call), but two calls whose stream work overlaps on one GPU race.  Calls on
+ *     one stream, or otherwise ordered, are safe. */
+#define PGMOE_STATIC_SCRATCH_BYTES (32u << 20)
+int pgmoe_expert_ffn_static(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_t *expert_offsets,
+                            int n_rows, void *y_perm, void *stream);
+
 /* ---- a-5: weighted combine -------------------------------------------------------------
  * y[t] = sum_{j<k} topk_prob[t,j] * y_perm[row_of[t*k+j]]  (gather form, no atomics, float32
  * accumulation, stored in ctx dtype).  If x_res and x_next are given, additionally

@@ -23,6 +23,7 @@ CACHE_LRU, CACHE_LFU, CACHE_LIFO = 0, 1, 2
 MAX_CACHE_SLOTS = 64
 MAX_PREGATE_DISTANCE = 3
 MAX_EXPERTS = 256
+STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = [
     "pgmoe_create", "pgmoe_destroy", "pgmoe_last_error", "pgmoe_expert_bytes", "pgmoe_workspace_bytes",
@@ -30,7 +31,7 @@ EXPORTS = [
     "pgmoe_register_resident_experts", "pgmoe_fetch_experts", "pgmoe_get_fetch_stats", "pgmoe_unique_experts",
     "pgmoe_permute", "pgmoe_expert_ffn", "pgmoe_combine", "pgmoe_stack_step", "pgmoe_device_flags",
     "pgmoe_ffn_timing_begin", "pgmoe_ffn_timing_end", "pgmoe_slot_address", "pgmoe_fetch_timing", "pgmoe_trace", "pgmoe_get_block_trace", "pgmoe_fetch_all_experts", "pgmoe_set_schedule",
-    "pgmoe_ffn_kernel_name", "pgmoe_set_nonmoe_standin", "pgmoe_check_streams",
+    "pgmoe_ffn_kernel_name", "pgmoe_set_nonmoe_standin", "pgmoe_check_streams", "pgmoe_expert_ffn_static",
 ]
 
 
@@ -94,6 +95,7 @@ def _load():
     L.pgmoe_unique_experts.argtypes = [vp, i, i, vp]
     L.pgmoe_permute.argtypes = [vp, vp, vp, i, vp, vp, vp, vp]
     L.pgmoe_expert_ffn.argtypes = [vp, i, vp, vp, i, vp, vp, vp]
+    L.pgmoe_expert_ffn_static.argtypes = [vp, i, vp, vp, i, vp, vp]
     L.pgmoe_combine.argtypes = [vp, vp, vp, vp, i, vp, vp, vp, vp]
     L.pgmoe_stack_step.argtypes = [vp, POINTER(StepBuffers), i, vp, vp]
     L.pgmoe_device_flags.argtypes = [vp, POINTER(c_uint32)]
@@ -232,6 +234,10 @@ class Context:
     def expert_ffn(self, block, x_perm, expert_offsets, n_rows, y_perm, workspace, stream=None):
         self._check(lib.pgmoe_expert_ffn(self._h, block, _ptr(x_perm), _ptr(expert_offsets), n_rows, _ptr(y_perm),
                                          _ptr(workspace), _stream(stream)))
+
+    def expert_ffn_static(self, block, x_perm, expert_offsets, n_rows, y_perm, stream=None):
+        self._check(lib.pgmoe_expert_ffn_static(self._h, block, _ptr(x_perm), _ptr(expert_offsets), n_rows, _ptr(y_perm),
+                                                _stream(stream)))
 
     def combine(self, y_perm, row_of, topk_prob, T, y, x_res=None, x_next=None, stream=None):
         self._check(lib.pgmoe_combine(self._h, _ptr(y_perm), _ptr(row_of), _ptr(topk_prob), T, _ptr(y), _ptr(x_res),

@@ -195,6 +195,7 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
             return fail(nullptr, PGMOE_ENODEVICE, "pgmoe_create: no HIP device is visible");
         }
         H(hipGetDevice(&c->device), "hipGetDevice");
+        if (rc == PGMOE_OK && (rc = resolve_static_scratch(c)) != PGMOE_OK) fail(nullptr, rc, "%s", c->err);
         const size_t flag_bytes = 64 + sizeof(int32_t) * (size_t)cfg->n_blocks;
         H(hipMalloc((void **)&c->dev_flags, flag_bytes), "hipMalloc(flags)");
         if (rc == PGMOE_OK) H(hipMemset(c->dev_flags, 0, flag_bytes), "hipMemset(flags)");

@@ -401,6 +401,24 @@ int pgmoe_expert_ffn(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_
     return expert_ffn_impl(ctx, block, x_perm, expert_offsets, n_rows, y_perm, workspace, stream, nullptr);
 }
 
+int pgmoe_expert_ffn_static(pgmoe_ctx *ctx, int block, const void *x_perm, const int32_t *expert_offsets, int n_rows,
+                            void *y_perm, void *stream) {
+    const char *fn = "pgmoe_expert_ffn_static";
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
+    const int64_t max_rows = (int64_t)ctx->cfg.max_tokens * ctx->cfg.top_k;
+    if (n_rows < 0 || n_rows > max_rows) return fail(ctx, PGMOE_EINVAL, "%s: n_rows=%d outside 0..%lld", fn, n_rows, (long long)max_rows);
+    const size_t need = ffn_launch_workspace_bytes(ctx->cfg, n_rows);
+    if (need > (size_t)PGMOE_STATIC_SCRATCH_BYTES)
+        return fail(ctx, PGMOE_EINVAL, "%s: a launch of %d rows needs %zu bytes of scratch, the static buffer has %zu: use pgmoe_expert_ffn "
+                    "with a workspace of the caller's", fn, n_rows, need, (size_t)PGMOE_STATIC_SCRATCH_BYTES);
+    if (ctx->host_only) {  // no device, no buffer: validate as pgmoe_expert_ffn does, with a stand-in address
+        alignas(256) static char host_stand_in[256];
+        return expert_ffn_impl(ctx, block, x_perm, expert_offsets, n_rows, y_perm, host_stand_in, stream, nullptr);
+    }
+    if (!ctx->static_scratch) return fail(ctx, PGMOE_ESTATE, "%s: the static scratch buffer was not resolved at pgmoe_create", fn);
+    return expert_ffn_impl(ctx, block, x_perm, expert_offsets, n_rows, y_perm, ctx->static_scratch, stream, nullptr);
+}
+
 // Stand-in for the non-MoE layers between two MoE blocks: one wavefront watches the constant
 // 100 MHz clock until `ticks` have passed; the loop is also bounded by a fixed number of clock
 // reads (each takes well over 10 ns), so the kernel ends in any case.

@@ -492,6 +492,37 @@ size_t ffn_workspace_bytes(const pgmoe_config &c) {
     return ((std::max(std::max(worst, big), gemm) + 255) & ~(size_t)255);
 }
 
+// Workspace bytes the launch of n_rows rows uses (what launch_ffn below writes and reads).
+size_t ffn_launch_workspace_bytes(const pgmoe_config &c, int n_rows) {
+    if (n_rows <= 0) return 0;
+    if (c.dtype == PGMOE_F32) return (size_t)n_rows * c.d_ff * 4;
+    if (uses_gemm_kernels(c, n_rows)) return ffn_gemm_launch_bytes(c, n_rows);
+    const FfnPlan p = plan_ffn(c, n_rows);
+    if (uses_decode_kernel(c, p) || p.n_partial > 1) return (size_t)p.n_partial * n_rows * c.d_model * 4;
+    return 0;
+}
+
+// Scratch of pgmoe_expert_ffn_static(): part of the library's device image, so no call ever
+// allocates it; every GPU the library runs on holds its own copy at its own address.  In host
+// code the array's name is only a handle for hipGetSymbolAddress: the address kernels and
+// copies take is resolved once per device, here, and kept.
+static __device__ __align__(256) unsigned char scratch[PGMOE_STATIC_SCRATCH_BYTES];
+static void *g_scratch_ptr[64] = {};
+
+int resolve_static_scratch(pgmoe_ctx *ctx) {  // the context's device is current (pgmoe_create)
+    const int dev = ctx->device;
+    if (dev < 0 || dev >= (int)(sizeof g_scratch_ptr / sizeof g_scratch_ptr[0]))
+        return fail(ctx, PGMOE_EINVAL, "pgmoe_create: device ordinal %d outside 0..63", dev);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        PG_HIP(ctx, hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || !aligned(ptr, 256)) return fail(ctx, PGMOE_EHIP, "pgmoe_create: the static scratch buffer resolved to %p", ptr);
+        g_scratch_ptr[dev] = ptr;
+    }
+    ctx->static_scratch = g_scratch_ptr[dev];
+    return PGMOE_OK;
+}
+
 int ffn_timing_slot(pgmoe_ctx *ctx) {
     if (!ctx->tim_on || ctx->tim_n >= ctx->tim_cap) return -1;
     return ctx->tim_n++;

@@ -103,6 +103,8 @@ int launch_ffn_reduce(pgmoe_ctx *ctx, const float *partial, int P, int n_rows, v
 bool uses_gemm_kernels(const pgmoe_config &c, int n_rows);
 // Workspace the two-GEMM path needs for max_tokens * top_k rows.
 size_t ffn_gemm_workspace_bytes(const pgmoe_config &c);
+// Workspace bytes one two-GEMM launch of n_rows rows uses.
+size_t ffn_gemm_launch_bytes(const pgmoe_config &c, int n_rows);
 // The two-GEMM path of launch_ffn (same arguments).
 int launch_ffn_gemm(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots, const void *x_rows,
                     const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s, int *keep_partials,

@@ -343,6 +343,21 @@ size_t ffn_gemm_workspace_bytes(const pgmoe_config &c) {
            (size_t)(max_rows / GEMM_ROWS + std::min<int64_t>(c.n_experts, max_rows)) * GEMM_ROWS * c.d_ff * 2 + 256;
 }
 
+// K slices of the down-projection: as few as still give every CU a workgroup (fewer float32
+// partials to write and to add up); one slice runs one workgroup per CU with a deeper ring, more
+// slices two per CU
+static int gemm_split(const pgmoe_config &c, int n_rows) {
+    const int tiles = (n_rows / GEMM_ROWS) * (c.d_model / GEMM_COLS);
+    return tiles >= 160 ? 1 : (tiles >= 80 ? 2 : GEMM_SPLIT);
+}
+
+// Workspace one launch of n_rows rows uses: the float32 partials, then the packed hidden activation.
+size_t ffn_gemm_launch_bytes(const pgmoe_config &c, int n_rows) {
+    const int active = std::max(1, std::min(c.n_experts, n_rows));
+    const int max_chunks = active + n_rows / GEMM_ROWS;
+    return (size_t)gemm_split(c, n_rows) * n_rows * c.d_model * 4 + (size_t)max_chunks * GEMM_ROWS * c.d_ff * 2;
+}
+
 int launch_ffn_gemm(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool slot_by_rank, int n_slots, const void *x_perm,
                     const int32_t *offsets, int n_rows, void *y_perm, void *workspace, hipStream_t s, int *keep_partials,
                     const unsigned long long *table, const int32_t *src_row) {
@@ -351,11 +366,7 @@ int launch_ffn_gemm(pgmoe_ctx *ctx, const char *w_base, size_t w_stride, bool sl
     // then the packed hidden activation, 128-row chunk by chunk (at most one partly filled chunk per expert)
     const int active = std::max(1, std::min(c.n_experts, n_rows));
     const int max_chunks = active + n_rows / GEMM_ROWS;
-    // K slices of the down-projection: as few as still give every CU a workgroup (fewer
-    // float32 partials to write and to add up); one slice runs one workgroup per CU with a
-    // deeper ring, more slices two per CU
-    const int tiles = (n_rows / GEMM_ROWS) * (c.d_model / GEMM_COLS);
-    const int split = tiles >= 160 ? 1 : (tiles >= 80 ? 2 : GEMM_SPLIT);
+    const int split = gemm_split(c, n_rows);
     const size_t p_bytes = (size_t)split * n_rows * c.d_model * 4;
     const size_t h_bytes = (size_t)max_chunks * GEMM_ROWS * c.d_ff * 2;
     if (h_bytes + p_bytes > ffn_workspace_bytes(c))

@@ -101,6 +101,8 @@ struct pgmoe_ctx {
     bool tim_on;
     float tim_overhead_ms;  // what one event pair adds around a kernel
 
+    void *static_scratch = nullptr;  // this device's copy of the library's static scratch buffer (pgmoe_expert_ffn_static)
+
     // kernels whose dynamic-LDS limit has been raised for this context's device (allow_dynamic_lds)
     const void *lds_ready[48] = {};
     int n_lds_ready = 0;
@@ -145,6 +147,10 @@ struct FfnPlan {
 };
 FfnPlan plan_ffn(const pgmoe_config &cfg, int n_rows);
 size_t ffn_workspace_bytes(const pgmoe_config &cfg);
+size_t ffn_launch_workspace_bytes(const pgmoe_config &cfg, int n_rows);  // what one launch of n_rows rows uses of it
+// Device address of the library's static scratch buffer on the context's device (which must be
+// current) into ctx->static_scratch; resolved once per device and process.
+int resolve_static_scratch(pgmoe_ctx *ctx);
 const char *ffn_kernel_name(const pgmoe_config &cfg, int n_rows);  // nullptr: no kernel is built for this launch
 bool ffn_supports_d_model(int d_model);                          // bf16: expert kernels are built for this d_model
 

@@ -115,6 +115,55 @@ def test_host_only_context_validates_then_refuses_to_launch():
     c.close()
 
 
+def test_static_scratch_ffn_validates_and_refuses_what_does_not_fit():
+    """pgmoe_expert_ffn_static on a host-only context (nothing can be launched, whatever the
+    verdict): argument checks as pgmoe_expert_ffn, and a launch whose partial sums or hidden
+    activation exceed the library's static buffer is refused with both sizes in the text."""
+    buf = np.zeros(1 << 16, dtype=np.uint8)
+    p = buf.ctypes.data + (-buf.ctypes.data) % 256
+    # float32: the hidden activation [rows, d_ff] in float32 is the scratch: 4096 x 4096 x 4 = 64 MiB
+    big_f32 = B.Context(cfg(dtype=B.F32, d_model=64, d_ff=4096, n_experts=4, top_k=1, max_tokens=4096))
+    eb = B.expert_bytes(big_f32.cfg)
+    big_f32.register_resident_experts(p, eb, 4 * eb)
+    with pytest.raises(B.PgmoeError) as ei:
+        big_f32.expert_ffn_static(0, p, p, 4096, p)
+    assert ei.value.code == B.EINVAL and str(B.STATIC_SCRATCH_BYTES) in str(ei.value) and str(4096 * 4096 * 4) in str(ei.value)
+    with pytest.raises(B.PgmoeError) as ei:
+        big_f32.expert_ffn_static(0, p, p, 2048, p)       # 32 MiB: fits exactly, so only the missing device stops it
+    assert ei.value.code == B.ENODEVICE
+    big_f32.close()
+    # bf16, 512 rows per expert (the two tiled GEMMs): float32 partials plus the packed hidden activation
+    gemm = B.Context(cfg(d_model=768, d_ff=3072, n_experts=8, top_k=1, max_tokens=4096))
+    eb = B.expert_bytes(gemm.cfg)
+    gemm.register_resident_experts(p, eb, 8 * eb)
+    assert "gemm" in gemm.ffn_kernel_name(4096)
+    with pytest.raises(B.PgmoeError) as ei:
+        gemm.expert_ffn_static(0, p, p, 4096, p)
+    assert ei.value.code == B.EINVAL and "pgmoe_expert_ffn" in str(ei.value)
+    # the same argument checks as pgmoe_expert_ffn
+    with pytest.raises(B.PgmoeError) as ei:
+        gemm.expert_ffn_static(0, p, p, 4097, p)
+    assert ei.value.code == B.EINVAL and "n_rows" in str(ei.value)
+    with pytest.raises(B.PgmoeError) as ei:
+        gemm.expert_ffn_static(1, p, p, 8, p)            # a valid call: only the missing device stops it
+    assert ei.value.code == B.ENODEVICE
+    with pytest.raises(B.PgmoeError) as ei:
+        gemm.expert_ffn_static(3, p, p, 8, p)
+    assert ei.value.code == B.EINVAL and "block" in str(ei.value)
+    with pytest.raises(B.PgmoeError) as ei:
+        gemm.expert_ffn_static(0, None, p, 8, p)
+    assert ei.value.code == B.EINVAL and "NULL" in str(ei.value)
+    with pytest.raises(B.PgmoeError) as ei:
+        gemm.expert_ffn_static(0, p + 2, p, 8, p)
+    assert ei.value.code == B.EINVAL and "misaligned" in str(ei.value)
+    gemm.close()
+    fresh = B.Context(cfg())
+    with pytest.raises(B.PgmoeError) as ei:
+        fresh.expert_ffn_static(0, p, p, 8, p)
+    assert ei.value.code == B.ESTATE                     # no store registered
+    fresh.close()
+
+
 def tiled_position(k, n, K, N, nt_major):
     """The layout rule of pgmoe.h retyped in numpy (vectorised over k, n)."""
     kt, nt = k // 32, n // 16
