@@ -136,7 +136,7 @@ def pmc_traffic(workload_name):
 
 
 def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gpu_only=True, systems=False,
-                 cache_frac=0.2, store=None, graphs=False, fetch_mode="pull"):
+                 cache_frac=0.2, store=None, graphs=False, fetch_mode="auto"):
     import numpy as np
     import torch
 
@@ -154,7 +154,11 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
     if own_store:
         store = H.ExpertStore(w, cfg, threads=host_threads)
     from paper_2308_12066_amd import binding as B
-    stack = H.Stack(w, store, flags=B.FLAG_FETCH_MEMCPY if fetch_mode == "memcpy" else 0)
+    # migration engine: the library's own choice by default (copy engines for large per-block
+    # migrations, the device-side pull kernel for small ones), or forced from the command line
+    mig_flags = {"auto": B.FLAG_FETCH_AUTO, "pull": 0, "memcpy": B.FLAG_FETCH_MEMCPY}[fetch_mode]
+    stack = H.Stack(w, store, flags=mig_flags)
+    engine = stack.ctx.migration_engine if w.offloaded else "none"
     # Every timed step gets its own hidden-state block (slice 0 pre-filled with that step's
     # input) and its own routing-index slice, so the timed loop holds library calls only.
     n_in = min(K, max(1, (1 << 30) // ((L + 1) * T * w.d_model * w.elem_bytes)))   # distinct inputs kept in HBM
@@ -247,8 +251,9 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         "config": {"workload": f"{w.name}: L={L} d_model={w.d_model} d_ff={w.d_ff} E={E} top{k} T={T}/step, "
                                f"experts {'offloaded to pinned host memory' if w.offloaded else 'resident in HBM'}",
                    "tokens_per_step": T, "blocks": L,
-                   "migration": ("hipMemcpyAsync per expert, issued by the host" if fetch_mode == "memcpy" else
-                                 "device-side pull kernel") if w.offloaded else "none"},
+                   "migration": {"copy_engine": "copy engines: one hipMemcpyAsync per expert, issued by the host once it has read "
+                                                "the routing back", "pull": "device-side pull kernel", "none": "none"}[engine]
+                                + (" (the library's choice for this configuration)" if fetch_mode == "auto" and w.offloaded else "")},
         "ms_per_token": 1e3 * dt / (T * K),
         "ms_per_token_per_layer": 1e3 * dt / (T * K * L),
         "block_latency_us": 1e6 * dt / (K * L),
@@ -274,7 +279,7 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         out["roofline"].update({"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                 "frac": tf / MFMA_BF16_PEAK_TFLOPS, "flops_per_launch": flops,
                                 "hbm_achieved_GBps": ffn_gbps, "hbm_frac": ffn_gbps / HBM_PEAK_GBPS})
-    if graphs and not (w.offloaded and fetch_mode == "memcpy"):   # the host-issued migration cannot be captured
+    if graphs and engine != "copy_engine":   # the host-issued migration cannot be captured
         out["graph_replay"] = graph_replay(stack, step_bufs[0], x_all[0, 0])
     if w.offloaded and trace_steps > 0:
         # pass 3: instrumented steps for the overlap figures (per-block events on both streams)
@@ -355,7 +360,22 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
             out["gpu_only"]["graph_replay"] = graph_replay(stack2, bufs2[0], x_all[0, 0])
         stack2.close()
         del stack2, bufs2
-    if w.offloaded and cache_frac > 0 and fetch_mode == "pull":
+    if w.offloaded and systems:
+        # The other migration engine on the same workload, same passes: what the choice costs and buys.
+        other = "pull" if engine == "copy_engine" else "copy_engine"
+        stk = H.Stack(w, store, flags=0 if other == "pull" else B.FLAG_FETCH_MEMCPY)
+        bufs = [stk.ctx.make_step_buffers(stk.gate_w, stk.gate_b, x_all[s % n_in], stk.y_blocks, idx_log[s], stk.topk_prob,
+                                          stk.row_of, stk.expert_offsets, stk.x_perm, stk.y_perm, stk.workspace) for s in range(K)]
+        dto, _, no, mso, oho = two_passes(stk, bufs)
+        uso = max(1e3 * mso / max(no, 1) - oho, 1e-3)
+        stk.close()
+        del stk, bufs
+
+        def engine_row(dt_, us_):
+            return {"tokens_per_s": T * K / dt_, "ms_per_step": 1e3 * dt_ / K, "host_link_GBps": h2d_bytes / dt_ / 1e9,
+                    "ffn_avg_launch_us": us_, "ffn_frac_of_hbm_peak": per_launch / (us_ * 1e-6) / 1e9 / HBM_PEAK_GBPS}
+        out["migration_engines"] = {engine: engine_row(dt, ffn_avg_us), other: engine_row(dto, uso), "used_for_value": engine}
+    if w.offloaded and cache_frac > 0:
         # Expert cache on top of the migration (the paper's caching study: a fraction of each
         # block's experts kept in HBM across steps; LRU here, all three policies for the headline
         # workload).  A labelled extra: `value` above is the base design without a cache.
@@ -363,7 +383,7 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         out["expert_cache"] = {"slots_per_block": C, "fraction_of_experts": C / E}
         pols = (("lru", B.CACHE_LRU), ("lfu", B.CACHE_LFU), ("lifo", B.CACHE_LIFO)) if systems else (("lru", B.CACHE_LRU),)
         for pname, pol in pols:
-            stk = H.Stack(w, store, cache_slots=C, cache_policy=pol)
+            stk = H.Stack(w, store, cache_slots=C, cache_policy=pol)     # the cache is kept by the pull kernel
             bufs = [stk.ctx.make_step_buffers(stk.gate_w, stk.gate_b, x_all[s % n_in], stk.y_blocks, idx_log[s],
                                               stk.topk_prob, stk.row_of, stk.expert_offsets, stk.x_perm, stk.y_perm,
                                               stk.workspace) for s in range(K)]
@@ -386,6 +406,9 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
                     sel += fs.n_unique
             out["expert_cache"][pname] = {"tokens_per_s": T * K / dtc, "ms_per_step": 1e3 * dtc / K,
                                           "speedup_vs_no_cache": dt / dtc, "hit_rate": hits / max(sel, 1)}
+            if "migration_engines" in out:    # against the uncached pull engine too (the cache lives in the pull kernel)
+                out["expert_cache"][pname]["speedup_vs_uncached_pull"] = \
+                    out["migration_engines"]["pull"]["ms_per_step"] / (1e3 * dtc / K)
             stk.close()
             del stk, bufs
     if w.offloaded and systems:
@@ -397,7 +420,7 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
                              "peak_resident_expert_MB": float((uniq[:, :-1] + uniq[:, 1:]).max() if L > 1 else uniq.max())
                              * w.expert_bytes / 1e6}}
         for sname, sched in (("on_demand", B.SCHED_ON_DEMAND), ("prefetch_all", B.SCHED_PREFETCH_ALL)):
-            stk = H.Stack(w, store, slots_per_gen=E if sched == B.SCHED_PREFETCH_ALL else 0)
+            stk = H.Stack(w, store, slots_per_gen=E if sched == B.SCHED_PREFETCH_ALL else 0, flags=mig_flags)
             stk.ctx.set_schedule(sched)
             bufs = [stk.ctx.make_step_buffers(stk.gate_w, stk.gate_b, x_all[s % n_in], stk.y_blocks, idx_log[s],
                                               stk.topk_prob, stk.row_of, stk.expert_offsets, stk.x_perm, stk.y_perm,
@@ -431,7 +454,7 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         for N in (2, 3):
             if N >= L:
                 continue
-            stk = H.Stack(w, store, pregate_distance=N)
+            stk = H.Stack(w, store, pregate_distance=N, flags=mig_flags)
             bufs = [stk.ctx.make_step_buffers(stk.gate_w, stk.gate_b, x_all[s % n_in], stk.y_blocks, idx_log[s],
                                               stk.topk_prob, stk.row_of, stk.expert_offsets, stk.x_perm, stk.y_perm,
                                               stk.workspace) for s in range(K)]
@@ -457,7 +480,7 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         sens = {}
         Kq = min(K, 32 if 1e3 * dt / K < 5.0 else 8)
         # one Stack for every row: the same streams, hence the same hardware queues, throughout
-        stk = H.Stack(w, store)
+        stk = H.Stack(w, store, flags=mig_flags)
         bufs = [stk.ctx.make_step_buffers(stk.gate_w, stk.gate_b, x_all[s % n_in], stk.y_blocks, idx_log[s],
                                           stk.topk_prob, stk.row_of, stk.expert_offsets, stk.x_perm, stk.y_perm,
                                           stk.workspace) for s in range(Kq)]
@@ -554,9 +577,9 @@ def main():
                     help="comma list of further workloads to summarise ('' for none); base8_prefill is the supplementary "
                          "shape with ~512 rows per expert, where the FFN is bound by the matrix cores")
     ap.add_argument("--all", action="store_true", help="also run the offloaded Switch-Base-128 prefill")
-    ap.add_argument("--fetch", default="pull", choices=("pull", "memcpy"),
-                    help="migration engine of the offloaded workloads: the device-side pull kernel (default) or one "
-                         "hipMemcpyAsync per expert issued by the host")
+    ap.add_argument("--fetch", default="auto", choices=("auto", "pull", "memcpy"),
+                    help="migration engine of the offloaded workloads: the library's choice by configuration (default), the "
+                         "device-side pull kernel, or one hipMemcpyAsync per expert issued by the host")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-steps", type=int, default=None)
     ap.add_argument("--trace-steps", type=int, default=8)

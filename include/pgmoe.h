@@ -68,6 +68,17 @@ typedef enum { PGMOE_F32 = 0, PGMOE_BF16 = 1 } pgmoe_dtype;
                                       by the host after it has read the routing indices back)
                                       instead of the default device-side pull kernel */
 
+#define PGMOE_FLAG_FETCH_AUTO 4u   /* let pgmoe_create pick the migration engine from the configuration: the
+                                      copy engines (as PGMOE_FLAG_FETCH_MEMCPY) when one block's migration can
+                                      reach PGMOE_AUTO_COPY_ENGINE_BYTES (slots_per_gen * expert bytes) and no
+                                      expert cache is configured, the pull kernel otherwise.  Why: the pull
+                                      kernel needs no host round trip and keeps the link busier (it wins by
+                                      5 % at one 9.4 MB expert per block, by 0.6 % at 25 experts of 16.8 MB),
+                                      but its host-link loads slow every kernel that reads HBM beside it (an
+                                      expert FFN by 1.5x, a plain read by 2.7x); copy-engine traffic does not
+                                      (1.08x).  pgmoe_migration_engine() tells which one a context uses. */
+#define PGMOE_AUTO_COPY_ENGINE_BYTES ((size_t)256 << 20)
+
 #define PGMOE_MAX_EXPERTS 256 /* the paper's largest model has 256 experts per block */
 
 typedef struct {
@@ -177,8 +188,11 @@ int pgmoe_register_resident_experts(pgmoe_ctx *ctx, const void *dev_base, size_t
  *       expert list and pulls the blobs out of the pinned host store over the host link.
  *       Nothing waits on the host: the call returns at once unless n_unique_out is given, in
  *       which case it blocks until the copy has finished and returns the count.
- *   PGMOE_FLAG_FETCH_MEMCPY : the host waits for the indices (small D2H copy), dedupes them
- *       and issues one hipMemcpyAsync per distinct expert.
+ *   PGMOE_FLAG_FETCH_MEMCPY (or PGMOE_FLAG_FETCH_AUTO on a context it gave the copy engines):
+ *       the host waits for the indices (small D2H copy), dedupes them and issues one
+ *       hipMemcpyAsync per distinct expert, dealt to two streams (copy_stream and the context's
+ *       own) so that one queue of copies fills the gaps the other leaves between two copies;
+ *       both streams take the blocks in order.
  * If more distinct experts are selected than slots_per_gen, memcpy mode returns
  * PGMOE_ENOSLOT; pull mode copies the first slots_per_gen of them, sets device flag bit 2 and
  * the FFN skips the rows of the others (their output rows are zero).
@@ -196,6 +210,9 @@ int pgmoe_fetch_experts(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int 
  * indices to wait for: the copy is ordered behind everything queued on compute_stream so far. */
 int pgmoe_fetch_all_experts(pgmoe_ctx *ctx, int block, void *compute_stream, void *copy_stream);
 int pgmoe_get_fetch_stats(pgmoe_ctx *ctx, int block, pgmoe_fetch_stats *out /* host */);
+/* The migration engine of this context: 0 = device-side pull kernel, 1 = copy engines
+ * (hipMemcpyAsync issued by the host); negative status if ctx is NULL. */
+int pgmoe_migration_engine(const pgmoe_ctx *ctx);
 /* Bracket every following fetch with a pair of timing events on the copy stream (fetch_ms of
  * pgmoe_fetch_stats).  Off by default: each event record costs microseconds between the
  * migration kernels of consecutive blocks. */
@@ -275,8 +292,9 @@ int pgmoe_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, con
  * The call only enqueues work (no host wait, no allocation, no memset) when the migration runs
  * in pull mode without an expert cache and neither tracing nor fetch timing is on, so it may be
  * captured into a HIP graph on compute_stream and replayed (the copy streams join the capture
- * through the call's own events and are joined back before it returns).  Not capturable:
- * PGMOE_FLAG_FETCH_MEMCPY (the host waits for the routing) and cache_slots > 0 (the cache
+ * through the call's own events and are joined back before it returns).  Not capturable: a
+ * context that migrates with the copy engines (PGMOE_FLAG_FETCH_MEMCPY, or the choice of
+ * PGMOE_FLAG_FETCH_AUTO; the host waits for the routing) and cache_slots > 0 (the cache
  * bookkeeping alternates between two device copies from call to call).
  * In pull mode the migrations of one call alternate between copy_stream and a second stream the
  * context owns, and their kernels take turns on the host link in block order (a device-side

@@ -18,6 +18,8 @@ F32, BF16 = 0, 1
 STREAMS_COMPUTE_COPY, STREAMS_COMPUTE_OWN, STREAMS_COPY_OWN = 1, 2, 4
 FLAG_HOST_ONLY = 1
 FLAG_FETCH_MEMCPY = 2
+FLAG_FETCH_AUTO = 4
+AUTO_COPY_ENGINE_BYTES = 256 << 20
 SCHED_PREGATED, SCHED_ON_DEMAND, SCHED_PREFETCH_ALL = 0, 1, 2
 CACHE_LRU, CACHE_LFU, CACHE_LIFO = 0, 1, 2
 MAX_CACHE_SLOTS = 64
@@ -31,7 +33,7 @@ EXPORTS = [
     "pgmoe_register_resident_experts", "pgmoe_fetch_experts", "pgmoe_get_fetch_stats", "pgmoe_unique_experts",
     "pgmoe_permute", "pgmoe_expert_ffn", "pgmoe_combine", "pgmoe_stack_step", "pgmoe_device_flags",
     "pgmoe_ffn_timing_begin", "pgmoe_ffn_timing_end", "pgmoe_slot_address", "pgmoe_fetch_timing", "pgmoe_trace", "pgmoe_get_block_trace", "pgmoe_fetch_all_experts", "pgmoe_set_schedule",
-    "pgmoe_ffn_kernel_name", "pgmoe_set_nonmoe_standin", "pgmoe_check_streams", "pgmoe_expert_ffn_static",
+    "pgmoe_ffn_kernel_name", "pgmoe_set_nonmoe_standin", "pgmoe_check_streams", "pgmoe_expert_ffn_static", "pgmoe_migration_engine",
 ]
 
 
@@ -92,6 +94,7 @@ def _load():
     L.pgmoe_register_resident_experts.argtypes = [vp, vp, c_size_t, c_size_t]
     L.pgmoe_fetch_experts.argtypes = [vp, i, vp, i, vp, vp, POINTER(c_int)]
     L.pgmoe_get_fetch_stats.argtypes = [vp, i, POINTER(FetchStats)]
+    L.pgmoe_migration_engine.argtypes = [vp]
     L.pgmoe_unique_experts.argtypes = [vp, i, i, vp]
     L.pgmoe_permute.argtypes = [vp, vp, vp, i, vp, vp, vp, vp]
     L.pgmoe_expert_ffn.argtypes = [vp, i, vp, vp, i, vp, vp, vp]
@@ -221,6 +224,12 @@ class Context:
         self._check(lib.pgmoe_fetch_experts(self._h, block, _ptr(topk_idx), T, _stream(compute_stream),
                                             _stream(copy_stream), byref(n)))
         return n.value
+
+    @property
+    def migration_engine(self) -> str:
+        rc = lib.pgmoe_migration_engine(self._h)
+        self._check(rc if rc < 0 else 0)
+        return "copy_engine" if rc == 1 else "pull"
 
     def fetch_stats(self, block) -> FetchStats:
         st = FetchStats()

@@ -50,7 +50,9 @@ int check_config(const pgmoe_config *c, char *buf, size_t n) {
         BAD("max_tokens=%d (x top_k=%d) outside 1..2^24", c->max_tokens, c->top_k);
     if (c->slots_per_gen < 0 || c->slots_per_gen > c->n_experts)
         BAD("slots_per_gen=%d outside 0..n_experts", c->slots_per_gen);
-    if (c->flags & ~(PGMOE_FLAG_HOST_ONLY | PGMOE_FLAG_FETCH_MEMCPY)) BAD("unknown flag bits 0x%x", c->flags);
+    if (c->flags & ~(PGMOE_FLAG_HOST_ONLY | PGMOE_FLAG_FETCH_MEMCPY | PGMOE_FLAG_FETCH_AUTO)) BAD("unknown flag bits 0x%x", c->flags);
+    if ((c->flags & PGMOE_FLAG_FETCH_MEMCPY) && (c->flags & PGMOE_FLAG_FETCH_AUTO))
+        BAD("PGMOE_FLAG_FETCH_MEMCPY and PGMOE_FLAG_FETCH_AUTO exclude each other");
     if (c->cache_slots < 0 || c->cache_slots > PGMOE_MAX_CACHE_SLOTS || c->cache_slots > c->n_experts)
         BAD("cache_slots=%d outside 0..min(%d, n_experts)", c->cache_slots, PGMOE_MAX_CACHE_SLOTS);
     if (c->cache_policy < PGMOE_CACHE_LRU || c->cache_policy > PGMOE_CACHE_LIFO) BAD("cache_policy=%d unknown", c->cache_policy);
@@ -161,10 +163,13 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
     if (!c) return fail(nullptr, PGMOE_EINVAL, "pgmoe_create: out of host memory");
     c->cfg = *cfg;
     c->host_only = (cfg->flags & PGMOE_FLAG_HOST_ONLY) != 0;
-    c->pull = (cfg->flags & PGMOE_FLAG_FETCH_MEMCPY) == 0;
     c->elem = cfg->dtype == PGMOE_F32 ? 4 : 2;
     c->expert_bytes = pgmoe_expert_bytes(cfg);
     c->slots = cfg->slots_per_gen > 0 ? cfg->slots_per_gen : default_slots(*cfg);
+    c->pull = (cfg->flags & PGMOE_FLAG_FETCH_MEMCPY) == 0;
+    if ((cfg->flags & PGMOE_FLAG_FETCH_AUTO) && cfg->cache_slots == 0 &&
+        (size_t)c->slots * c->expert_bytes >= PGMOE_AUTO_COPY_ENGINE_BYTES)
+        c->pull = false;
     c->distance = cfg->pregate_distance > 0 ? cfg->pregate_distance : 1;
     c->n_gen = c->distance + 1;
     c->store_mode = STORE_NONE;
@@ -212,6 +217,8 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
             // these two only order device work against device work: no host-visible release needed
             H(hipEventCreateWithFlags(&c->fetch_done[g], hipEventDisableTiming | hipEventReleaseToDevice), "hipEventCreate");
             H(hipEventCreateWithFlags(&c->ffn_done[g], hipEventDisableTiming | hipEventReleaseToDevice), "hipEventCreate");
+            H(hipEventCreateWithFlags(&c->fork[g], hipEventDisableTiming | hipEventReleaseToDevice), "hipEventCreate");
+            H(hipEventCreateWithFlags(&c->join[g], hipEventDisableTiming | hipEventReleaseToDevice), "hipEventCreate");
         }
         if (rc == PGMOE_OK) {
             hipEvent_t **arrays[] = {&c->fetch_begin, &c->fetch_end, &c->ev_c0, &c->ev_ready, &c->ev_waited, &c->ev_c1};
@@ -253,6 +260,8 @@ int pgmoe_destroy(pgmoe_ctx *c) {
         for (int g = 0; g < kGen; ++g) {
             if (c->fetch_done[g]) (void)hipEventDestroy(c->fetch_done[g]);
             if (c->ffn_done[g]) (void)hipEventDestroy(c->ffn_done[g]);
+            if (c->fork[g]) (void)hipEventDestroy(c->fork[g]);
+            if (c->join[g]) (void)hipEventDestroy(c->join[g]);
         }
         hipEvent_t *arrays[] = {c->fetch_begin, c->fetch_end, c->ev_c0, c->ev_ready, c->ev_waited, c->ev_c1};
         for (hipEvent_t *a : arrays) {
@@ -388,6 +397,11 @@ int pgmoe_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, con
     NEED_DEVICE(ctx, fn);
     if (T == 0) return PGMOE_OK;
     return launch_combine(ctx, y_perm, row_of, topk_prob, T, y, x_res, x_next, (hipStream_t)stream);
+}
+
+int pgmoe_migration_engine(const pgmoe_ctx *ctx) {
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "pgmoe_migration_engine: ctx is NULL");
+    return ctx->pull ? 0 : 1;
 }
 
 const char *pgmoe_ffn_kernel_name(const pgmoe_ctx *ctx, int n_rows) {

@@ -207,11 +207,26 @@ static int fetch_impl(pgmoe_ctx *ctx, const char *fn, int block, bool all, const
     rc = wait_for_last_reader(ctx, gen, cs, ps);
     if (rc) return rc;
     if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_begin[block], ps));
+    // The copies of one block are dealt to two streams, the one chosen above and the other of the
+    // pair (caller's copy stream, the context's own): a copy engine leaves the link idle for a few
+    // microseconds between two dependent copies of one stream, and a second queue of copies fills
+    // those gaps.  Both streams take every block's copies in block order, so the blocks still
+    // arrive one after the other.
+    hipStream_t ps2 = ps == ctx->copy2 ? (hipStream_t)copy_stream : ctx->copy2;
+    const bool two = !inline_fetch && nu > 1 && ps2 != ps && ps2 != cs;
+    if (two) {
+        PG_HIP(ctx, hipEventRecord(ctx->fork[gen], ps));  // behind everything ps has waited for
+        PG_HIP(ctx, hipStreamWaitEvent(ps2, ctx->fork[gen], 0));
+    }
     char *gen_base = ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes;
     const char *src_block = ctx->store_base + (size_t)block * ctx->block_stride;
     for (int j = 0; j < nu; ++j)
         PG_HIP(ctx, hipMemcpyAsync(gen_base + (size_t)j * ctx->expert_bytes, src_block + (size_t)uniq[j] * ctx->expert_stride,
-                                   ctx->expert_bytes, hipMemcpyHostToDevice, ps));
+                                   ctx->expert_bytes, hipMemcpyHostToDevice, (two && (j & 1)) ? ps2 : ps));
+    if (two) {
+        PG_HIP(ctx, hipEventRecord(ctx->join[gen], ps2));
+        PG_HIP(ctx, hipStreamWaitEvent(ps, ctx->join[gen], 0));
+    }
     if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_end[block], ps));
     if (!inline_fetch) PG_HIP(ctx, hipEventRecord(ctx->fetch_done[gen], ps));
 

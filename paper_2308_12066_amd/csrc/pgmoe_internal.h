@@ -69,6 +69,7 @@ struct pgmoe_ctx {
     hipEvent_t idx_ready;
     hipEvent_t fetch_done[pgmoe::kGen];
     hipEvent_t ffn_done[pgmoe::kGen];
+    hipEvent_t fork[pgmoe::kGen], join[pgmoe::kGen];  // memcpy mode: a block's copies go out on two streams
     hipEvent_t *fetch_begin;  // [n_blocks] timing
     hipEvent_t *fetch_end;    // [n_blocks]
     int fetched_block[pgmoe::kGen];  // block whose experts the generation holds (-1: none)

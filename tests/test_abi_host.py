@@ -56,6 +56,24 @@ def test_create_rejects_more_than_the_pull_kernels_can_address():
     B.Context(cfg(**dict(big, flags=B.FLAG_HOST_ONLY | B.FLAG_FETCH_MEMCPY))).close()
 
 
+def test_automatic_choice_of_the_migration_engine():
+    """PGMOE_FLAG_FETCH_AUTO: copy engines once a block's migration can reach 256 MiB (slots x expert
+    bytes) and no expert cache is configured, the pull kernel otherwise; explicit flags are obeyed."""
+    large = dict(d_model=1024, d_ff=4096, n_experts=128, top_k=1, max_tokens=64, n_blocks=12)    # 64 slots x 16.8 MB
+    base8 = dict(d_model=768, d_ff=3072, n_experts=8, top_k=1, max_tokens=1, n_blocks=6)         # 1 slot x 9.4 MB
+    for kw, flags, want in ((large, B.FLAG_FETCH_AUTO, "copy_engine"), (base8, B.FLAG_FETCH_AUTO, "pull"),
+                            (large, 0, "pull"), (base8, B.FLAG_FETCH_MEMCPY, "copy_engine"),
+                            (dict(large, cache_slots=8), B.FLAG_FETCH_AUTO, "pull"),
+                            (dict(large, slots_per_gen=15), B.FLAG_FETCH_AUTO, "pull"),          # 15 x 16 MiB < 256 MiB
+                            (dict(large, slots_per_gen=16), B.FLAG_FETCH_AUTO, "copy_engine")):
+        c = B.Context(cfg(**kw, flags=B.FLAG_HOST_ONLY | flags))
+        assert c.migration_engine == want, (kw, flags)
+        c.close()
+    with pytest.raises(B.PgmoeError) as ei:
+        B.Context(cfg(flags=B.FLAG_HOST_ONLY | B.FLAG_FETCH_AUTO | B.FLAG_FETCH_MEMCPY))
+    assert ei.value.code == B.EINVAL and "exclude" in str(ei.value)
+
+
 def test_expert_bytes():
     assert B.expert_bytes(cfg(d_model=768, d_ff=3072)) == 9437184
     assert B.expert_bytes(cfg(d_model=1024, d_ff=4096)) == 16777216

@@ -1,6 +1,6 @@
 """GPU parity at the full size of the stated workloads: every block of the stack, every token,
-in the launch configuration the benchmark times (pull-mode migration without fetch timing or
-tracing unless a case says otherwise).
+in the launch configuration the benchmark times (the migration engine the library picks for the
+configuration, no fetch timing, no tracing) unless a case says otherwise.
 
 Each block is checked in shadow mode against the CPU oracle (the oracle evaluates block i on the
 GPU's own x_{i-1} for the routing and x_i for the experts).  Expert weights are regenerated from
@@ -56,7 +56,10 @@ class RegeneratedExperts:
 def run_case(H, B, name, store, steps, fetch, timing, first_step=0):
     w = W.CONFIGS[name]
     gates = W.gate_tensors(w)
-    stack = H.Stack(w, store, gates=gates, flags=B.FLAG_FETCH_MEMCPY if fetch == "memcpy" else 0)
+    stack = H.Stack(w, store, gates=gates, flags={"memcpy": B.FLAG_FETCH_MEMCPY, "auto": B.FLAG_FETCH_AUTO}.get(fetch, 0))
+    if fetch == "auto":      # what the benchmark runs: the library picks the engine from the configuration
+        assert stack.ctx.migration_engine == ("copy_engine" if w.top_k * w.tokens * w.expert_bytes >= B.AUTO_COPY_ENGINE_BYTES
+                                              and w.n_experts * w.expert_bytes >= B.AUTO_COPY_ENGINE_BYTES else "pull")
     stack.ctx.fetch_timing(timing)
     experts = RegeneratedExperts(w)
     near = tot = 0
@@ -90,10 +93,10 @@ def test_switch_large_128_all_twelve_blocks_top1_and_top2(hx):
     w = W.CONFIGS["cfg5"]
     say(f"full depth: Switch-Large-128, L={w.n_blocks}, building the expert store")
     store = H.ExpertStore(w, H.config_for(w), threads=HOST_THREADS)
-    run_case(H, B, "cfg5", store, steps=2, fetch="pull", timing=False)
+    run_case(H, B, "cfg5", store, steps=2, fetch="auto", timing=False)
     run_case(H, B, "cfg5_top2", store, steps=2, fetch="pull", timing=False)
-    run_case(H, B, "cfg5_top2", store, steps=1, fetch="memcpy", timing=True, first_step=2)
-    run_case(H, B, "cfg5", store, steps=1, fetch="memcpy", timing=False, first_step=2)
+    run_case(H, B, "cfg5_top2", store, steps=1, fetch="auto", timing=True, first_step=2)
+    run_case(H, B, "cfg5", store, steps=1, fetch="pull", timing=False, first_step=2)
 
 
 def test_switch_base_128_prefill_all_six_blocks_resident_and_offloaded(hx):
@@ -104,7 +107,7 @@ def test_switch_base_128_prefill_all_six_blocks_resident_and_offloaded(hx):
     say(f"full depth: Switch-Base-128 prefill, L={w.n_blocks}, building the expert store")
     store = H.ExpertStore(w, H.config_for(w), threads=HOST_THREADS)
     run_case(H, B, "cfg4", store, steps=1, fetch="-", timing=False)
-    run_case(H, B, "cfg4_offloaded", store, steps=1, fetch="pull", timing=False)
+    run_case(H, B, "cfg4_offloaded", store, steps=1, fetch="auto", timing=False)
 
 
 def test_switch_base_8_and_64_decode_over_many_steps(hx):
@@ -114,4 +117,4 @@ def test_switch_base_8_and_64_decode_over_many_steps(hx):
     for name, steps in (("cfg2", 32), ("cfg3", 8)):
         w = W.CONFIGS[name]
         store = H.ExpertStore(w, H.config_for(w), threads=HOST_THREADS)
-        run_case(H, B, name, store, steps=steps, fetch="pull", timing=False)
+        run_case(H, B, name, store, steps=steps, fetch="auto", timing=False)
