@@ -284,7 +284,7 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
     if w.offloaded and trace_steps > 0:
         # pass 3: instrumented steps for the overlap figures (per-block events on both streams)
         stack.ctx.trace(True)
-        busy = busy0 = stall = stall0 = comp = fsum = 0.0
+        busy = busy0 = stall = stall0 = comp = fsum = csum = cbytes = 0.0
         for s in range(trace_steps):
             stack.ctx.stack_step(step_bufs[s % K], T, stack.compute, stack.copy)
             torch.cuda.synchronize()
@@ -301,12 +301,18 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
             stall0 += tr[0].stall_ms
             comp += sum(t.compute_ms for t in tr)
             fsum += sum(t.fetch_ms for t in tr)
+            csum += sum(t.copy_ms for t in tr)
+            cbytes += float(uniq[s % K].sum()) * w.expert_bytes
         stack.ctx.trace(False)
         n = float(trace_steps)
         out["overlap"] = {
             "steps": trace_steps,
             "link_busy_ms_per_step": busy / n, "stall_ms_per_step": stall / n, "compute_ms_per_step": comp / n,
             "sum_of_fetch_durations_ms_per_step": fsum / n,
+            # the copies alone (the pull kernel's own clock readings, without its wait for the turn on the
+            # link; with the copy engines the events around a block's copies): bytes / time = link rate
+            "sum_of_copy_times_ms_per_step": csum / n,
+            "link_GBps_while_copying": cbytes / max(csum, 1e-9) / 1e6,
             "hidden_frac": 1.0 - stall / busy,
             "hidden_frac_without_block0": 1.0 - (stall - stall0) / max(busy - busy0, 1e-9),
             "hidden_frac_upper_bound": min(1.0, comp / busy),

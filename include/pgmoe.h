@@ -222,6 +222,18 @@ int pgmoe_fetch_timing(pgmoe_ctx *ctx, int enable);
  * expert).  dev_out host. */
 int pgmoe_slot_address(pgmoe_ctx *ctx, int block, int slot, void **dev_out);
 
+/* Test hook for the bounded wait of the pull engine.  Inside pgmoe_stack_step the migration
+ * kernels of a step take turns on the host link: kernel number seq starts copying when the seq
+ * kernels before it have passed the turn on, or when its wait has lasted half a second (the
+ * wait orders link traffic only; no result depends on it).  This call runs the migration of
+ * `block` on `stream`, in stream order, as kernel number seq of a step that has no other
+ * kernels, with the wait bounded by wait_us microseconds (1 .. 500000) instead: nobody passes
+ * the turn on, so for seq > 0 the kernel waits that long, gives up, copies and leaves normally.
+ * Otherwise as pgmoe_fetch_experts(ctx, block, topk_idx, T, stream, stream, NULL).  Pull engine
+ * and host store only (PGMOE_ESTATE otherwise). */
+int pgmoe_fetch_experts_as_turn(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int T, void *stream,
+                                int seq, float wait_us);
+
 /* Host-only helper used by the fetch engine, exported for testing: ascending list of the
  * distinct values of idx[0..n) (all must lie in [0, E)); returns their number or a negative
  * status.  unique_out host [min(E, n)]. */
@@ -397,11 +409,15 @@ int pgmoe_ffn_timing_end(pgmoe_ctx *ctx, int *n_out, float *total_ms_out, float 
  *   compute_ms duration of the block on the compute stream (pre-gate, grouping, FFN, combine)
  *              minus stall_ms;
  *   fetch_start_ms, fetch_end_ms, block_start_ms, block_end_ms: the same events as offsets
- *              from the start of block 0 on the compute stream. */
+ *              from the start of block 0 on the compute stream;
+ *   copy_ms    the copy alone: from the moment the migration kernel starts copying (its turn has
+ *              come) to the return of its last load, by the kernel's own readings of the 100 MHz
+ *              clock; bytes_copied / copy_ms is the link rate of that migration.  With the copy
+ *              engines it equals fetch_ms. */
 typedef struct {
     float fetch_ms, stall_ms, compute_ms;
     float fetch_start_ms, fetch_end_ms, block_start_ms, block_end_ms;
-    float reserved;
+    float copy_ms;
 } pgmoe_block_trace;
 int pgmoe_trace(pgmoe_ctx *ctx, int enable);
 int pgmoe_get_block_trace(pgmoe_ctx *ctx, int block, pgmoe_block_trace *out /* host */);

@@ -33,7 +33,7 @@ EXPORTS = [
     "pgmoe_register_resident_experts", "pgmoe_fetch_experts", "pgmoe_get_fetch_stats", "pgmoe_unique_experts",
     "pgmoe_permute", "pgmoe_expert_ffn", "pgmoe_combine", "pgmoe_stack_step", "pgmoe_device_flags",
     "pgmoe_ffn_timing_begin", "pgmoe_ffn_timing_end", "pgmoe_slot_address", "pgmoe_fetch_timing", "pgmoe_trace", "pgmoe_get_block_trace", "pgmoe_fetch_all_experts", "pgmoe_set_schedule",
-    "pgmoe_ffn_kernel_name", "pgmoe_set_nonmoe_standin", "pgmoe_check_streams", "pgmoe_expert_ffn_static", "pgmoe_migration_engine",
+    "pgmoe_ffn_kernel_name", "pgmoe_set_nonmoe_standin", "pgmoe_check_streams", "pgmoe_expert_ffn_static", "pgmoe_migration_engine", "pgmoe_fetch_experts_as_turn",
 ]
 
 
@@ -51,7 +51,7 @@ class FetchStats(Structure):
 
 class BlockTrace(Structure):
     _fields_ = [("fetch_ms", c_float), ("stall_ms", c_float), ("compute_ms", c_float), ("fetch_start_ms", c_float),
-                ("fetch_end_ms", c_float), ("block_start_ms", c_float), ("block_end_ms", c_float), ("reserved", c_float)]
+                ("fetch_end_ms", c_float), ("block_start_ms", c_float), ("block_end_ms", c_float), ("copy_ms", c_float)]
 
 
 class StepBuffers(Structure):
@@ -93,6 +93,7 @@ def _load():
     L.pgmoe_register_host_experts.argtypes = [vp, vp, c_size_t, c_size_t]
     L.pgmoe_register_resident_experts.argtypes = [vp, vp, c_size_t, c_size_t]
     L.pgmoe_fetch_experts.argtypes = [vp, i, vp, i, vp, vp, POINTER(c_int)]
+    L.pgmoe_fetch_experts_as_turn.argtypes = [vp, i, vp, i, vp, i, c_float]
     L.pgmoe_get_fetch_stats.argtypes = [vp, i, POINTER(FetchStats)]
     L.pgmoe_migration_engine.argtypes = [vp]
     L.pgmoe_unique_experts.argtypes = [vp, i, i, vp]
@@ -224,6 +225,9 @@ class Context:
         self._check(lib.pgmoe_fetch_experts(self._h, block, _ptr(topk_idx), T, _stream(compute_stream),
                                             _stream(copy_stream), byref(n)))
         return n.value
+
+    def fetch_experts_as_turn(self, block, topk_idx, T, stream, seq: int, wait_us: float):
+        self._check(lib.pgmoe_fetch_experts_as_turn(self._h, block, _ptr(topk_idx), T, _stream(stream), seq, wait_us))
 
     @property
     def migration_engine(self) -> str:

@@ -201,10 +201,12 @@ int pgmoe_create(pgmoe_ctx **out, const pgmoe_config *cfg) {
         }
         H(hipGetDevice(&c->device), "hipGetDevice");
         if (rc == PGMOE_OK && (rc = resolve_static_scratch(c)) != PGMOE_OK) fail(nullptr, rc, "%s", c->err);
-        const size_t flag_bytes = 64 + sizeof(int32_t) * (size_t)cfg->n_blocks;
+        // sticky flags and turn counters (64 bytes), then per block: copy clocks (2 x 8 bytes), distinct-expert count
+        const size_t flag_bytes = 64 + (2 * sizeof(unsigned long long) + sizeof(int32_t)) * (size_t)cfg->n_blocks;
         H(hipMalloc((void **)&c->dev_flags, flag_bytes), "hipMalloc(flags)");
         if (rc == PGMOE_OK) H(hipMemset(c->dev_flags, 0, flag_bytes), "hipMemset(flags)");
-        c->dev_unique = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(c->dev_flags) + 64);
+        c->dev_copy_clock = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(c->dev_flags) + 64);
+        c->dev_unique = reinterpret_cast<int32_t *>(c->dev_copy_clock + 2 * (size_t)cfg->n_blocks);
         size_t n_idx = (size_t)cfg->max_tokens * cfg->top_k;
         if (rc == PGMOE_OK) H(hipMalloc((void **)&c->dev_src_row, (size_t)cfg->n_blocks * n_idx * sizeof(int32_t)), "hipMalloc(src_row)");
         if (rc == PGMOE_OK) H(hipHostMalloc((void **)&c->idx_staging, n_idx * sizeof(int32_t), hipHostMallocDefault), "hipHostMalloc(idx staging)");

@@ -152,7 +152,7 @@ static int fetch_impl(pgmoe_ctx *ctx, const char *fn, int block, bool all, const
         if (rc) return rc;
         if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_begin[block], ps));
         const int seq = ctx->pull_seq >= 0 ? ctx->pull_seq++ : -1;  // inside a step: its place in the queue for the link
-        rc = launch_fetch_pull(ctx, block, all, topk_idx, n, ps, seq, seq >= 0 && seq == ctx->pull_last);
+        rc = launch_fetch_pull(ctx, block, all, topk_idx, n, ps, seq, seq >= 0 && seq == ctx->pull_last, ctx->turn_timeout_ticks);
         if (rc) return rc;
         if (ctx->fetch_timing) PG_HIP(ctx, hipEventRecord(ctx->fetch_end[block], ps));
         if (!inline_fetch) PG_HIP(ctx, hipEventRecord(ctx->fetch_done[gen], ps));
@@ -258,6 +258,25 @@ int pgmoe_fetch_all_experts(pgmoe_ctx *ctx, int block, void *compute_stream, voi
     return fetch_impl(ctx, "pgmoe_fetch_all_experts", block, true, nullptr, 0, compute_stream, copy_stream, nullptr);
 }
 
+int pgmoe_fetch_experts_as_turn(pgmoe_ctx *ctx, int block, const int32_t *topk_idx, int T, void *stream, int seq, float wait_us) {
+    const char *fn = "pgmoe_fetch_experts_as_turn";
+    if (!ctx) return fail(nullptr, PGMOE_EINVAL, "%s: ctx is NULL", fn);
+    if (seq < 0 || seq > 4096) return fail(ctx, PGMOE_EINVAL, "%s: seq=%d outside 0..4096", fn, seq);
+    if (!(wait_us >= 1.f && wait_us <= 500000.f)) return fail(ctx, PGMOE_EINVAL, "%s: wait_us=%g outside 1..500000", fn, (double)wait_us);
+    if (ctx->store_mode != STORE_HOST || !ctx->pull)
+        return fail(ctx, PGMOE_ESTATE, "%s: needs a host expert store and the pull engine", fn);
+    // an exposed fetch in stream order (compute == copy stream), as migration number seq of a step
+    // that has no other migrations: fetch_impl hands seq on to the kernel and the scope guard ends the "step"
+    struct Scope {
+        pgmoe_ctx *c;
+        ~Scope() { c->pull_seq = c->pull_last = -1; c->turn_timeout_ticks = 0; }
+    } scope{ctx};
+    ctx->pull_seq = seq;
+    ctx->pull_last = seq;  // it is also the "step's" last kernel: its last workgroup sets the turn counter back to 0
+    ctx->turn_timeout_ticks = (unsigned long long)(wait_us * 100.f);
+    return fetch_impl(ctx, fn, block, false, topk_idx, T, stream, stream, nullptr);
+}
+
 int pgmoe_set_schedule(pgmoe_ctx *ctx, int schedule) {
     if (!ctx) return fail(nullptr, PGMOE_EINVAL, "pgmoe_set_schedule: ctx is NULL");
     if (schedule < PGMOE_SCHED_PREGATED || schedule > PGMOE_SCHED_PREFETCH_ALL)
@@ -354,6 +373,14 @@ int pgmoe_get_block_trace(pgmoe_ctx *ctx, int block, pgmoe_block_trace *out) {
     PG_HIP(ctx, el(ctx->ev_c0[0], ctx->fetch_end[block], &out->fetch_end_ms));
     PG_HIP(ctx, el(ctx->ev_c0[0], ctx->ev_c0[block], &out->block_start_ms));
     PG_HIP(ctx, el(ctx->ev_c0[0], ctx->ev_c1[block], &out->block_end_ms));
+    // the copy itself: the pull kernel's own clock readings (its duration above includes the wait for
+    // its turn on the link); the copy engines have no such wait, their copies span fetch_ms
+    out->copy_ms = out->fetch_ms;
+    if (ctx->stats[block].pulled) {
+        unsigned long long clk[2] = {0, 0};
+        PG_HIP(ctx, hipMemcpy(clk, ctx->dev_copy_clock + 2 * (size_t)block, sizeof clk, hipMemcpyDeviceToHost));
+        out->copy_ms = clk[1] > clk[0] ? (float)((double)(clk[1] - clk[0]) * 1e-5) : 0.f;  // 100 MHz ticks
+    }
     out->stall_ms = stall > 0.f ? stall : 0.f;
     // a fetch on the compute stream itself is waited for in stream order, not at the event wait
     if (ctx->stats[block].in_line) out->stall_ms += out->fetch_ms;

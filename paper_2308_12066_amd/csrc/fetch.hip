@@ -37,15 +37,15 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 // step replays with the same arguments; the step's first kernel clears it as well, which limits
 // what a late straggler of the previous step (or a step that ended early) can leave behind to one
 // pair of kernels copying side by side.
-constexpr unsigned long long TURN_TIMEOUT_TICKS = 50000000ull;  // of the 100 MHz wall clock
+constexpr unsigned long long TURN_TIMEOUT_TICKS = 50000000ull;  // of the 100 MHz wall clock: the bound inside a stack step
 
-__device__ inline void wait_for_turn(uint32_t *turn, int seq) {
+__device__ inline void wait_for_turn(uint32_t *turn, int seq, unsigned long long timeout_ticks) {
     if (seq == 0 && blockIdx.x == 0 && threadIdx.x == 0) __hip_atomic_store(turn, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (seq <= 0) return;  // uniform over the kernel
     if (threadIdx.x == 0) {
         const unsigned long long t0 = wall_clock64();
         while (__hip_atomic_load(turn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)seq &&
-               wall_clock64() - t0 < TURN_TIMEOUT_TICKS)
+               wall_clock64() - t0 < timeout_ticks)
             __builtin_amdgcn_s_sleep(32);
     }
     __syncthreads();
@@ -64,11 +64,24 @@ __device__ inline void end_of_turn(uint32_t *turn, int seq, int last) {
     }
 }
 
+// With tracing on, a migration kernel leaves the 100 MHz clock of the moment it starts copying
+// (first workgroup, after its wait for the turn) in clk[0] and of the moment its last workgroup
+// has its last load back in clk[1] (a maximum: the clock only grows, so an earlier migration's
+// value never wins): the copy itself, without the wait that the kernel's duration includes.
+__device__ inline void copy_clock_begin(unsigned long long *clk) {
+    if (clk && blockIdx.x == 0 && threadIdx.x == 0) __hip_atomic_store(clk, wall_clock64(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void copy_clock_end(unsigned long long *clk) {
+    if (!clk) return;  // uniform over the kernel
+    __syncthreads();   // every load of this workgroup has returned (its value went into a store)
+    if (threadIdx.x == 0) atomicMax(clk + 1, wall_clock64());
+}
+
 template <typename V>
 __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_kernel(
     const int32_t *__restrict__ idx, int n, int E, const char *__restrict__ src_block, size_t expert_stride,
     char *__restrict__ gen_base, size_t expert_bytes, int slots, int all, int32_t *__restrict__ unique_out,
-    uint32_t *flags, uint32_t *turn, int seq, int last) {
+    uint32_t *flags, uint32_t *turn, int seq, int last, unsigned long long turn_timeout, unsigned long long *clk) {
     __shared__ int present[PGMOE_MAX_EXPERTS];
     __shared__ int list[PGMOE_MAX_EXPERTS];
     __shared__ int s_u;
@@ -96,7 +109,8 @@ __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_kernel(
         if (U > slots) atomicOr(flags, kFlagNoSlot);
     }
     if (U > slots) U = slots;
-    wait_for_turn(turn, seq);
+    wait_for_turn(turn, seq, turn_timeout);
+    copy_clock_begin(clk);
 
     // all selected blobs form one range of U * upe vector units, dealt out grid-stride
     const unsigned upe = (unsigned)(expert_bytes / sizeof(V));
@@ -122,6 +136,7 @@ __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_kernel(
         reinterpret_cast<V *>(gen_base + (size_t)sl * expert_bytes)[of] =
             reinterpret_cast<const V *>(src_block + (size_t)list[sl] * expert_stride)[of];
     }
+    copy_clock_end(clk);
     end_of_turn(turn, seq, last);
 }
 
@@ -154,7 +169,8 @@ __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_cache_kernel(
     const int32_t *__restrict__ idx, int n, int E, const char *__restrict__ src_block, size_t expert_stride,
     char *__restrict__ gen_base, size_t expert_bytes, int slots, char *__restrict__ cache_base, int C, int policy,
     const int32_t *__restrict__ state_in, int32_t *__restrict__ state_out, unsigned long long *__restrict__ table,
-    int32_t *__restrict__ stats_out, uint32_t *flags, uint32_t *turn, int seq, int last) {
+    int32_t *__restrict__ stats_out, uint32_t *flags, uint32_t *turn, int seq, int last, unsigned long long turn_timeout,
+    unsigned long long *clk) {
     __shared__ int present[PGMOE_MAX_EXPERTS];               // 0 not selected, 1 selected
     __shared__ int cp_src[PGMOE_MAX_EXPERTS];                // copies: source expert
     __shared__ unsigned long long cp_dst[PGMOE_MAX_EXPERTS]; // copies: destination address
@@ -257,7 +273,8 @@ __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_cache_kernel(
     __syncthreads();
     if (blockIdx.x == 0)
         for (int e = tid; e < E; e += FETCH_THREADS) table[e] = tbl[e];
-    wait_for_turn(turn, seq);
+    wait_for_turn(turn, seq, turn_timeout);
+    copy_clock_begin(clk);
 
     const unsigned upe = (unsigned)(expert_bytes / sizeof(V));
     const unsigned total = (unsigned)s_counts[0] * upe;
@@ -267,13 +284,17 @@ __global__ __launch_bounds__(FETCH_THREADS) void fetch_pull_cache_kernel(
         reinterpret_cast<V *>(cp_dst[j])[of] =
             __builtin_nontemporal_load(reinterpret_cast<const V *>(src_block + (size_t)cp_src[j] * expert_stride) + of);
     }
+    copy_clock_end(clk);
     end_of_turn(turn, seq, last);
 }
 
 size_t cache_state_bytes(const pgmoe_config &c) { return (size_t)c.n_blocks * 2 * CACHE_STATE_INTS * sizeof(int32_t); }
 
-int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, int n, hipStream_t s, int seq, bool last) {
+int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, int n, hipStream_t s, int seq, bool last,
+                      unsigned long long turn_timeout_ticks) {
     const int gen = block % ctx->n_gen;
+    const unsigned long long tmo = turn_timeout_ticks ? turn_timeout_ticks : TURN_TIMEOUT_TICKS;
+    unsigned long long *clk = ctx->trace ? ctx->dev_copy_clock + 2 * (size_t)block : nullptr;
     uint32_t *turn = ctx->dev_flags + 4;  // two counters in the flag block's first 64 bytes
     const int is_last = last ? 1 : 0;
     char *gen_base = ctx->slot_pool + (size_t)gen * ctx->slots * ctx->expert_bytes;
@@ -288,11 +309,11 @@ int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, i
         if (ctx->expert_bytes % 16 == 0)
             hipLaunchKernelGGL(fetch_pull_cache_kernel<u32x4>, dim3(FETCH_GRID), dim3(FETCH_THREADS), 0, s, idx, n,
                                ctx->cfg.n_experts, src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, cache_base,
-                               C, ctx->cfg.cache_policy, st_in, st_out, table, stats, ctx->dev_flags, turn, seq, is_last);
+                               C, ctx->cfg.cache_policy, st_in, st_out, table, stats, ctx->dev_flags, turn, seq, is_last, tmo, clk);
         else
             hipLaunchKernelGGL(fetch_pull_cache_kernel<unsigned int>, dim3(FETCH_GRID), dim3(FETCH_THREADS), 0, s, idx, n,
                                ctx->cfg.n_experts, src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, cache_base,
-                               C, ctx->cfg.cache_policy, st_in, st_out, table, stats, ctx->dev_flags, turn, seq, is_last);
+                               C, ctx->cfg.cache_policy, st_in, st_out, table, stats, ctx->dev_flags, turn, seq, is_last, tmo, clk);
         PG_HIP(ctx, hipGetLastError());
         ctx->cache_parity[block] = par ^ 1;
         return PGMOE_OK;
@@ -300,11 +321,11 @@ int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, i
     if (ctx->expert_bytes % 16 == 0)
         hipLaunchKernelGGL(fetch_pull_kernel<u32x4>, dim3(FETCH_GRID), dim3(FETCH_THREADS), 0, s, idx, n, ctx->cfg.n_experts,
                            src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, all ? 1 : 0, ctx->dev_unique + block,
-                           ctx->dev_flags, turn, seq, is_last);
+                           ctx->dev_flags, turn, seq, is_last, tmo, clk);
     else
         hipLaunchKernelGGL(fetch_pull_kernel<unsigned int>, dim3(FETCH_GRID), dim3(FETCH_THREADS), 0, s, idx, n,
                            ctx->cfg.n_experts, src, ctx->expert_stride, gen_base, ctx->expert_bytes, ctx->slots, all ? 1 : 0,
-                           ctx->dev_unique + block, ctx->dev_flags, turn, seq, is_last);
+                           ctx->dev_unique + block, ctx->dev_flags, turn, seq, is_last, tmo, clk);
     PG_HIP(ctx, hipGetLastError());
     return PGMOE_OK;
 }

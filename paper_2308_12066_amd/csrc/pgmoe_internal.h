@@ -54,11 +54,13 @@ struct pgmoe_ctx {
     char *slot_pool;       // [n_gen][slots][expert_bytes]
     uint32_t *dev_flags;   // [0] sticky condition bits; [4], [5] turn counters of the migration kernels (fetch.hip)
     int32_t *dev_unique;   // [n_blocks] distinct experts found by the pull kernel (dev_flags + 64 bytes)
+    unsigned long long *dev_copy_clock;  // [n_blocks][2] copy start / end of the block's last traced pull kernel (100 MHz ticks)
     int32_t *dev_src_row;  // [n_blocks][max_tokens * k] grouped row -> token, written by each block's routing
     bool *routed;          // [n_blocks] host: this step's gate kernel already grouped the block's tokens
     // turn-taking of a stack step's migration kernels on the host link (see fetch.hip): position of
     // the next one in the step (-1: not inside a step), and the position of the step's last one
     int pull_seq = -1, pull_last = -1;
+    unsigned long long turn_timeout_ticks = 0;  // bound of the wait for the turn (0 = default); set by the test hook only
     // set by pgmoe_stack_step around one fetch: the routing was computed on the copy stream the
     // fetch will use (stream order covers it), so no event from the compute stream is needed
     bool routed_on_copy_stream = false;
@@ -195,8 +197,9 @@ int launch_combine_partials(pgmoe_ctx *ctx, const float *partial, int P, int n_r
                             const float *prob, int T, void *y, const void *x_res, void *x_next, hipStream_t s);
 // seq: position among the migration kernels of the running stack step (they take turns on the
 // host link in that order), -1 for a kernel that is not part of one; last: the step's last one
+// turn_timeout_ticks: bound of that wait in ticks of the 100 MHz clock (0 = the default of half a second)
 int launch_fetch_pull(pgmoe_ctx *ctx, int block, bool all, const int32_t *idx, int n, hipStream_t s, int seq = -1,
-                      bool last = false);
+                      bool last = false, unsigned long long turn_timeout_ticks = 0);
 size_t cache_state_bytes(const pgmoe_config &c);
 int launch_combine(pgmoe_ctx *ctx, const void *y_perm, const int32_t *row_of, const float *prob, int T,
                    void *y, const void *x_res, void *x_next, hipStream_t s);
