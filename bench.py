@@ -124,6 +124,46 @@ def measured_peaks():
     return {"hbm_copy_read_plus_write_GBps": d2d, "h2d_pinned_256MiB_GBps": h2d}
 
 
+def vendor_gemm_context(w):
+    """Context only, never part of `value`: what the vendor's GEMM library (hipBLASLt behind torch.bmm)
+    needs for the same two products with the rows dealt evenly to the experts, and for one large
+    square product: how much of the published matrix-core peak a tuned library delivers on this
+    box for this shape and for its best case."""
+    import torch
+    E, M, d, f = w.n_experts, w.tokens * w.top_k // w.n_experts, w.d_model, w.d_ff
+
+    def timed(fn, n=40):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n * 1e3
+
+    g = torch.Generator(device="cuda").manual_seed(1)
+    x = torch.randn(E, M, d, device="cuda", dtype=torch.bfloat16, generator=g)
+    w1 = torch.randn(E, d, f, device="cuda", dtype=torch.bfloat16, generator=g) * 0.02
+    w2 = torch.randn(E, f, d, device="cuda", dtype=torch.bfloat16, generator=g) * 0.02
+    h = torch.empty(E, M, f, device="cuda", dtype=torch.bfloat16)
+    y = torch.empty(E, M, d, device="cuda", dtype=torch.bfloat16)
+    up = timed(lambda: torch.bmm(x, w1, out=h))
+    down = timed(lambda: torch.bmm(h, w2, out=y))
+    n = 8192
+    a = torch.randn(n, n, device="cuda", dtype=torch.bfloat16, generator=g)
+    c = torch.empty(n, n, device="cuda", dtype=torch.bfloat16)
+    sq = timed(lambda: torch.mm(a, a, out=c), 10)
+    flops = 4.0 * E * M * d * f
+    return {"up_us": up, "down_us": down, "both_TFLOPs": flops / (up + down) / 1e6,
+            "both_frac_of_mfma_peak": flops / (up + down) / 1e6 / MFMA_BF16_PEAK_TFLOPS,
+            "square_8192_TFLOPs": 2.0 * n ** 3 / sq / 1e6, "square_8192_frac_of_mfma_peak": 2.0 * n ** 3 / sq / 1e6 / MFMA_BF16_PEAK_TFLOPS,
+            "note": f"torch.bmm (vendor GEMM library) on [{E}, {M}, {d}] x [{E}, {d}, {f}] and [{E}, {M}, {f}] x [{E}, {f}, {d}], "
+                    "back-to-back launches, no ReLU, no routing; and torch.mm on 8192^3: a measuring stick for the peak, not a code path"}
+
+
 def pmc_traffic(workload_name):
     """HBM bytes per FFN launch from the committed rocprofv3 --pmc summary, if there is one."""
     path = os.path.join(ROOT, "profiles", "expert_ffn_hbm_traffic.md")
@@ -279,6 +319,8 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         out["roofline"].update({"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                 "frac": tf / MFMA_BF16_PEAK_TFLOPS, "flops_per_launch": flops,
                                 "hbm_achieved_GBps": ffn_gbps, "hbm_frac": ffn_gbps / HBM_PEAK_GBPS})
+        if gpu_only:     # not in the --main-only runs the profiler summaries are taken from
+            out["roofline"]["vendor_library_context"] = vendor_gemm_context(w)
     if graphs and engine != "copy_engine":   # the host-issued migration cannot be captured
         out["graph_replay"] = graph_replay(stack, step_bufs[0], x_all[0, 0])
     if w.offloaded and trace_steps > 0:

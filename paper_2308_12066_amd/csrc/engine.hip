@@ -176,6 +176,14 @@ static int fetch_impl(pgmoe_ctx *ctx, const char *fn, int block, bool all, const
         return PGMOE_OK;
     }
 
+    // The host waits for the routing below: under stream capture nothing executes, so that wait
+    // would never end.  Refuse before anything is queued.
+    {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(cs, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)
+            return fail(ctx, PGMOE_ESTATE, "%s: this context migrates with the copy engines (the host reads the routing back), which cannot "
+                        "be captured into a graph; create the context without PGMOE_FLAG_FETCH_MEMCPY / PGMOE_FLAG_FETCH_AUTO", fn);
+    }
     // 1. bring the indices to the host (the only host wait of the block)
     const auto t0 = std::chrono::steady_clock::now();
     if (all && !inline_fetch) {

@@ -616,6 +616,30 @@ def test_stack_step_replays_from_a_captured_graph(hx, offloaded, shape):
     stack.close()
 
 
+def test_a_copy_engine_context_refuses_to_be_captured(hx):
+    """With the copy engines the host waits for the routing inside the call; under stream capture
+    nothing runs, so the call must refuse (before it queues anything) instead of waiting for ever."""
+    H, B = hx
+    w = small_workload("bf16", 6, 128, 256, 8, 2, L=3, offloaded=True, index=54)
+    stack, gates, cache = make_stack(H, w, flags=B.FLAG_FETCH_MEMCPY)
+    stack.set_input(W.step_input(w, 0))
+    stack.step()
+    torch.cuda.synchronize()
+    want = stack.x_states.clone()
+    graph = torch.cuda.CUDAGraph()
+    with pytest.raises(B.PgmoeError) as ei:
+        with torch.cuda.graph(graph, stream=stack.compute):
+            stack.ctx.fetch_experts(0, stack.topk_idx[0], w.tokens, stack.compute, stack.copy)
+    assert ei.value.code == B.ESTATE and "captured" in str(ei.value)
+    del graph
+    torch.cuda.synchronize()
+    stack.x_states[1:].zero_()
+    stack.step()                                     # and the context still works
+    torch.cuda.synchronize()
+    assert torch.equal(stack.x_states.view(torch.int16), want.view(torch.int16))
+    stack.close()
+
+
 def test_nonmoe_standin_changes_the_time_not_the_results(hx):
     """The clock-watching stand-in for the non-MoE layers only occupies the compute stream."""
     import time
