@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the pre-gated MoE hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--also cfg5_top2,cfg2,...] [--all]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--also cfg5_top2,cfg2,...] [--all] [--no-sweep-k]
 
 A "step" is one pass of the whole hot path over one batch: conventional gate of block 0,
 pre-gates, migration of the pre-gated experts from pinned host memory, token grouping,
@@ -176,7 +176,10 @@ def pmc_traffic(workload_name):
 
 
 def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gpu_only=True, systems=False,
-                 cache_frac=0.2, store=None, graphs=False, fetch_mode="auto"):
+                 cache_frac=0.2, store=None, graphs=False, fetch_mode="auto", extras=None):
+    """systems: also the paper's comparison systems on this workload; extras (default: as systems): also the
+    other migration engine, pre-gate distance 2/3 and the non-MoE stand-in rows."""
+    extras = systems if extras is None else extras
     import numpy as np
     import torch
 
@@ -408,7 +411,7 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
             out["gpu_only"]["graph_replay"] = graph_replay(stack2, bufs2[0], x_all[0, 0])
         stack2.close()
         del stack2, bufs2
-    if w.offloaded and systems:
+    if w.offloaded and extras:
         # The other migration engine on the same workload, same passes: what the choice costs and buys.
         other = "pull" if engine == "copy_engine" else "copy_engine"
         stk = H.Stack(w, store, flags=0 if other == "pull" else B.FLAG_FETCH_MEMCPY)
@@ -495,6 +498,7 @@ def run_workload(name, K, Wm, host_threads, with_cpu, cpu_steps, trace_steps, gp
         for v in comp.values():
             v["block_latency_vs_pregated"] = v["block_latency_us"] / base
         out["systems"] = comp
+    if w.offloaded and systems and extras:
         # Pre-gate looking N = 2 / 3 blocks ahead (the paper's activation-level study, system
         # side): experts are requested N blocks early and N + 1 generations stay resident.
         dist = {"1": {"tokens_per_s": T * K / dt, "block_latency_us": 1e6 * dt / (K * L),
@@ -603,7 +607,8 @@ def activated_expert_sweep(host_threads, steps):
     # later point pays the first access to a blob of the pinned store inside its timed steps
     # (with one expert per block and step, the two warm-up steps would leave most blobs untouched)
     for k in sorted(W.SWEEP_K, reverse=True):
-        r = run_workload(f"sweep64_k{k}", steps, 2, host_threads, False, None, 0, systems=True, cache_frac=0.0, store=store)
+        r = run_workload(f"sweep64_k{k}", steps, 2, host_threads, False, None, 0, systems=True, cache_frac=0.0, store=store,
+                         extras=False)
         sysm = r["systems"]
         g = sysm["gpu_only"]["block_latency_us"]
         rows[str(k)] = {n: {"block_latency_us": v["block_latency_us"], "vs_gpu_only": v["block_latency_us"] / g,
@@ -635,8 +640,9 @@ def main():
     ap.add_argument("--main-only", action="store_true",
                     help="only the timed passes of --workload (no GPU-only, cache, comparison-system or distance passes): "
                          "what the rocprofv3 summaries under profiles/ are taken from")
-    ap.add_argument("--sweep-k", action="store_true",
-                    help="add the activated-expert sweep (top-1..64 on the Switch-Base-64 shape, four systems)")
+    ap.add_argument("--no-sweep-k", action="store_true",
+                    help="leave out the activated-expert sweep (top-1..64 on the Switch-Base-64 shape, four systems)")
+    ap.add_argument("--sweep-steps", type=int, default=8)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -693,8 +699,8 @@ def main():
                          fetch_mode=args.fetch)
         drop_store(n)
         out["other_workloads"][n] = {k: r[k] for k in keep if k in r}
-    if args.sweep_k:
-        out["activated_expert_sweep"] = activated_expert_sweep(args.host_threads, 16)
+    if not args.no_sweep_k and not args.main_only:
+        out["activated_expert_sweep"] = activated_expert_sweep(args.host_threads, args.sweep_steps)
     print(json.dumps(out), flush=True)
 
 
