@@ -23,6 +23,8 @@
 //   tokens the B operand, so each lane ends up with 4 consecutive features of one token.
 //
 // f32 path - plain float32 kernels (correctness configuration; no matrix cores).
+#include <mutex>
+
 #include "ffn_common.h"
 #include "gate_small.h"
 
@@ -508,11 +510,13 @@ size_t ffn_launch_workspace_bytes(const pgmoe_config &c, int n_rows) {
 // copies take is resolved once per device, here, and kept.
 static __device__ __align__(256) unsigned char scratch[PGMOE_STATIC_SCRATCH_BYTES];
 static void *g_scratch_ptr[64] = {};
+static std::mutex g_scratch_mutex;  // contexts may be created from several host threads
 
 int resolve_static_scratch(pgmoe_ctx *ctx) {  // the context's device is current (pgmoe_create)
     const int dev = ctx->device;
     if (dev < 0 || dev >= (int)(sizeof g_scratch_ptr / sizeof g_scratch_ptr[0]))
         return fail(ctx, PGMOE_EINVAL, "pgmoe_create: device ordinal %d outside 0..63", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
     if (!g_scratch_ptr[dev]) {
         void *ptr = nullptr;
         PG_HIP(ctx, hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
