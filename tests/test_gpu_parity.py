@@ -994,6 +994,19 @@ def test_expert_cache_changes_the_copies_not_the_results(hx, policy, shape, dist
                 f"step {s} block {b}: device {(fs.n_unique, fs.cache_hits, fs.n_copied)} vs model {ref}"
             assert fs.bytes_copied == len(ref["copies"]) * w.expert_bytes
             hits_total += fs.cache_hits
+    # the trace of a cached stack: every block's copy time (the cache-aware kernel's own clock readings)
+    # lies inside the kernel's duration, and a block that copied nothing spent next to no time copying
+    cached.ctx.trace(True)
+    cached.set_input(W.step_input(w, 0))
+    cached.step()
+    torch.cuda.synchronize()
+    for b in range(w.n_blocks):
+        tr, fs = cached.ctx.block_trace(b), cached.ctx.fetch_stats(b)
+        models[b].fetch(np.unique(cached.topk_idx[b].cpu().numpy()))      # keep the reference model in step
+        assert 0.0 <= tr.copy_ms <= tr.fetch_ms + 0.05, (b, tr.copy_ms, tr.fetch_ms)
+        if fs.n_copied == 0:
+            assert tr.copy_ms < 0.05
+    cached.ctx.trace(False)
     say(f"  cache {policy}: {hits_total} hits over 10 steps x {w.n_blocks} blocks")
     assert hits_total > 0
     assert cached.ctx.device_flags() == 0
