@@ -91,8 +91,8 @@ typedef struct {
     int32_t max_tokens;    /* largest T of any call */
     int32_t dtype;         /* pgmoe_dtype of activations, gate weights and expert weights */
     int32_t slots_per_gen; /* expert slots per block generation; 0 => min(E, max_tokens*k),
-                              which can never overflow.  Ignored without a host store.  Unless
-                              PGMOE_FLAG_FETCH_MEMCPY is set, (slots + cache_slots) * expert bytes
+                              which can never overflow.  Ignored without a host store.  On a context
+                              that migrates with the pull kernel, (slots + cache_slots) * expert bytes
                               must stay below 64 GiB (32-bit unit numbers in the pull kernels). */
     uint32_t flags;
     int32_t cache_slots;   /* expert cache on top of the migration (Sec. VI "Caching experts"): slots

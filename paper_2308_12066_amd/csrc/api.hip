@@ -60,11 +60,13 @@ int check_config(const pgmoe_config *c, char *buf, size_t n) {
         BAD("pregate_distance=%d outside 0..%d", c->pregate_distance, PGMOE_MAX_PREGATE_DISTANCE);
     if (c->cache_slots > 0 && (c->flags & PGMOE_FLAG_FETCH_MEMCPY))
         BAD("the expert cache is kept by the device-side pull engine: not available with PGMOE_FLAG_FETCH_MEMCPY");
-    if (!(c->flags & PGMOE_FLAG_FETCH_MEMCPY)) {
+    const uint64_t eb = (uint64_t)2 * c->d_model * c->d_ff * (c->dtype == PGMOE_F32 ? 4 : 2);
+    const uint64_t slots = c->slots_per_gen > 0 ? c->slots_per_gen : default_slots(*c);
+    // (the same rule pgmoe_create applies)
+    const bool auto_copy_engines = (c->flags & PGMOE_FLAG_FETCH_AUTO) && c->cache_slots == 0 && slots * eb >= PGMOE_AUTO_COPY_ENGINE_BYTES;
+    if (!(c->flags & PGMOE_FLAG_FETCH_MEMCPY) && !auto_copy_engines) {
         // the pull kernels number the 16-byte (4-byte if the blob is no multiple of 16) units of
         // everything one migration may copy with 32 bits
-        const uint64_t eb = (uint64_t)2 * c->d_model * c->d_ff * (c->dtype == PGMOE_F32 ? 4 : 2);
-        const uint64_t slots = c->slots_per_gen > 0 ? c->slots_per_gen : default_slots(*c);
         if ((slots + c->cache_slots) * (eb / (eb % 16 ? 4 : 16)) >= (1ull << 32) - (1ull << 20))
             BAD("%llu slots of %llu-byte experts are more than one device-side migration can address: fewer slots_per_gen, "
                 "or PGMOE_FLAG_FETCH_MEMCPY", (unsigned long long)(slots + c->cache_slots), (unsigned long long)eb);

@@ -53,6 +53,9 @@ def test_create_rejects_more_than_the_pull_kernels_can_address():
         B.Context(cfg(**big))
     assert ei.value.code == B.EINVAL and "PGMOE_FLAG_FETCH_MEMCPY" in str(ei.value)
     B.Context(cfg(**big, slots_per_gen=3)).close()
+    auto = B.Context(cfg(**dict(big, flags=B.FLAG_HOST_ONLY | B.FLAG_FETCH_AUTO)))       # picks the copy engines at that size
+    assert auto.migration_engine == "copy_engine"
+    auto.close()
     B.Context(cfg(**dict(big, flags=B.FLAG_HOST_ONLY | B.FLAG_FETCH_MEMCPY))).close()
 
 
