@@ -56,3 +56,57 @@ def test_static_scratch_ffn_equals_the_workspace_ffn(dtype, d, f, E, first, seco
         assert names[0] != names[1]      # the two calls went through different kernels
     assert ctx.device_flags() == 0
     ctx.close()
+
+
+def test_static_scratch_ffn_replays_from_a_captured_graph():
+    """What the entry point is for: grouping, expert FFN and combine captured into one HIP graph
+    with no workspace to bring, replayed several times with the program's own eager work in
+    between; every replay gives the bits the eager calls give."""
+    from paper_2308_12066_amd import binding as B, harness as H
+    T, d, f, E, k = 24, 768, 3072, 8, 2
+    w = W.Workload("static_graph", 79, 1, d, f, E, k, T, 1, "bf16", 0.0, False)
+    cfg = H.config_for(w)
+    store = H.ExpertStore(w, cfg, threads=4)
+    ctx = B.Context(cfg)
+    ctx.register_resident_experts(store.to_hbm(), store.expert_stride, store.block_stride)
+    g = np.random.default_rng(3)
+    xs = [H.to_device(W.round_to_bf16(g.standard_normal((T, d)).astype(np.float32)), "bf16") for _ in range(3)]
+    idx = torch.from_numpy(np.stack([g.choice(E, size=k, replace=False) for _ in range(T)]).astype(np.int32)).cuda()
+    prob = torch.from_numpy(g.random((T, k)).astype(np.float32)).cuda()
+    x = torch.zeros((T, d), dtype=torch.bfloat16, device="cuda")
+    x_perm, y_perm = torch.zeros((T * k, d), dtype=torch.bfloat16, device="cuda"), torch.zeros((T * k, d), dtype=torch.bfloat16, device="cuda")
+    row_of = torch.zeros(T * k, dtype=torch.int32, device="cuda")
+    offs = torch.zeros(E + 1, dtype=torch.int32, device="cuda")
+    y = torch.zeros((T, d), dtype=torch.bfloat16, device="cuda")
+    stream = torch.cuda.Stream()
+
+    def block():
+        ctx.permute(x, idx, T, x_perm, row_of, offs, stream)
+        ctx.expert_ffn_static(0, x_perm, offs, T * k, y_perm, stream)
+        ctx.combine(y_perm, row_of, prob, T, y, None, None, stream)
+
+    eager = []
+    for xi in xs:                                    # eager results; also warms every kernel up
+        x.copy_(xi)
+        torch.cuda.synchronize()
+        block()
+        torch.cuda.synchronize()
+        eager.append(y.clone())
+    assert not torch.equal(eager[0], eager[1])
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=stream):
+        block()
+    torch.cuda.synchronize()
+    for rep in range(2):
+        for xi, want in zip(xs, eager):
+            x.copy_(xi)
+            y.zero_()                                # eager work between the replays
+            y_perm.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y.view(torch.int16), want.view(torch.int16)), f"replay {rep}"
+    del graph
+    assert ctx.device_flags() == 0
+    ctx.close()
