@@ -388,7 +388,7 @@ int pgmoe_stack_step(pgmoe_ctx *ctx, const pgmoe_step_buffers *io, int T, void *
  * n_out, total_ms_out host; pair_overhead_ms_out host | NULL. */
 int pgmoe_ffn_timing_begin(pgmoe_ctx *ctx, int max_launches);
 /* Name of the main kernel pgmoe_expert_ffn() launches for n_rows permuted rows in this context
- * ("ffn_decode_kernel", "ffn_fused_kernel", "ffn_gemm_up_kernel+ffn_gemm_down_kernel" or
+ * ("ffn_decode_kernel", "ffn_fused_kernel", "ffn_gemm_pack_rows_kernel+ffn_gemm_tile_kernel" or
  * "ffn_f32_hidden_kernel+ffn_f32_out_kernel"): the
  * name to look for in a profiler's kernel trace.  Static string; NULL if ctx is NULL or no kernel
  * is built for that launch (pgmoe_expert_ffn() would return PGMOE_EINVAL; no accepted

@@ -41,7 +41,7 @@ FLAGS = [
 # spill or any other scratch access the compiler added would be one more vector-memory operation
 # in that count and a stage could be read from LDS before it has landed.  The build fails if one
 # of them uses scratch memory.
-NO_SCRATCH_KERNELS = ("ffn_gemm_down_kernel",)
+NO_SCRATCH_KERNELS = ("ffn_gemm_tile_kernel",)
 
 
 def resource_usage(remarks: str) -> dict:

@@ -4,7 +4,7 @@
 // bf16 path - three kernels, picked from the shape of the launch alone (plan_ffn and friends):
 //   ffn_fused_kernel   the general, HBM-bound case (described next);
 //   ffn_decode_kernel  a handful of active experts with <= 16 rows each (batch-1 decode);
-//   ffn_gemm_up_kernel + ffn_gemm_down_kernel  hundreds of rows per expert: two tiled GEMMs (ffn_gemm.hip).
+//   ffn_gemm_pack_rows_kernel + ffn_gemm_tile_kernel (twice)  hundreds of rows per expert: two tiled GEMMs (ffn_gemm.hip).
 // The fused kernel streams the weights from HBM exactly once per 16*MT-row chunk:
 //   workgroup = (chunk of <= 16*MT rows of one expert) x (a range of d_ff columns)
 //   = (blockIdx.x, blockIdx.y).
@@ -478,7 +478,7 @@ static bool uses_decode_kernel(const pgmoe_config &c, const FfnPlan &p) {
 
 const char *ffn_kernel_name(const pgmoe_config &c, int n_rows) {
     if (c.dtype == PGMOE_F32) return "ffn_f32_hidden_kernel+ffn_f32_out_kernel";
-    if (uses_gemm_kernels(c, n_rows)) return "ffn_gemm_up_kernel+ffn_gemm_down_kernel";
+    if (uses_gemm_kernels(c, n_rows)) return "ffn_gemm_pack_rows_kernel+ffn_gemm_tile_kernel";
     const FfnPlan p = plan_ffn(c, n_rows);
     if (uses_decode_kernel(c, p)) return "ffn_decode_kernel";
     return fused_case_built(p.mt, c.d_model / 32, p.nw) && c.d_ff % (16 * p.nw) == 0 ? "ffn_fused_kernel" : nullptr;

@@ -290,5 +290,5 @@ def test_ffn_kernel_name_follows_the_launch_plan():
     assert name(1, d_model=768, d_ff=3072, n_experts=8, top_k=1, max_tokens=1) == "ffn_decode_kernel"
     assert name(4096, d_model=768, d_ff=3072, n_experts=128, top_k=1, max_tokens=4096) == "ffn_fused_kernel"
     assert name(16, d_model=768, d_ff=3072, n_experts=64, top_k=1, max_tokens=16) == "ffn_fused_kernel"
-    assert name(4096, d_model=768, d_ff=3072, n_experts=8, top_k=1, max_tokens=4096) == "ffn_gemm_up_kernel+ffn_gemm_down_kernel"   # ~512 rows per expert
+    assert name(4096, d_model=768, d_ff=3072, n_experts=8, top_k=1, max_tokens=4096) == "ffn_gemm_pack_rows_kernel+ffn_gemm_tile_kernel"   # ~512 rows per expert
     assert name(8, d_model=64, d_ff=256, n_experts=8, top_k=1, dtype=B.F32) == "ffn_f32_hidden_kernel+ffn_f32_out_kernel"
