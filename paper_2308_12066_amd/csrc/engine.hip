@@ -318,16 +318,17 @@ int pgmoe_get_fetch_stats(pgmoe_ctx *ctx, int block, pgmoe_fetch_stats *out) {
         if (st.pulled) {
             // the pull kernel left the distinct-expert counts on the device
             PG_HIP(ctx, hipStreamSynchronize(ctx->fetch_stream[block % ctx->n_gen]));
-            int32_t u0 = 0;
-            PG_HIP(ctx, hipMemcpy(&u0, ctx->dev_unique + block, sizeof(int32_t), hipMemcpyDeviceToHost));
+            // the counts of this block and of the N blocks that execute before it, in one copy
+            int32_t u[PGMOE_MAX_PREGATE_DISTANCE + 1] = {};
+            const int first = block - ctx->distance > 0 ? block - ctx->distance : 0;
+            PG_HIP(ctx, hipMemcpy(u, ctx->dev_unique + first, sizeof(int32_t) * (size_t)(block - first + 1), hipMemcpyDeviceToHost));
+            const int32_t u0 = u[block - first];
             int copied = u0 < ctx->slots ? u0 : ctx->slots;
             st.s.n_unique = u0;
             st.s.resident_slots = copied;
-            // plus the generations of the N blocks that execute before this one
-            for (int b = block - 1; b >= 0 && b >= block - ctx->distance; --b) {
+            for (int b = block - 1; b >= first; --b) {
                 if (!ctx->stats[b].pulled) continue;
-                int32_t ub = 0;
-                PG_HIP(ctx, hipMemcpy(&ub, ctx->dev_unique + b, sizeof(int32_t), hipMemcpyDeviceToHost));
+                const int32_t ub = u[b - first];
                 st.s.resident_slots += ub < ctx->slots ? ub : ctx->slots;
             }
             if (st.cached) {  // unique, copies, hits as the cache-aware kernel counted them
